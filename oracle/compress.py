@@ -1,0 +1,152 @@
+"""Oracle for Stage 2b of SurfaceLogicKV: KV entry selection (test infrastructure).
+
+Follows Section 3.1 (Eq. 2-4), Section 3.4 (Eq. 7-8) and Algorithm 3 of the
+paper, in float64, one (sequence, KV head) segment at a time, with no tiling,
+fusion or reordering.  The paper leaves several points open; the readings used
+here are:
+
+  * softmax runs over the history keys only (Algorithm 3 forms the history H
+    first and takes Softmax(Q_window H^T / sqrt(d_k)) of it);
+  * the w x m probability matrix is reduced to one score per history key by
+    summing over the w window rows, and under grouped-query attention over the
+    G query heads that share the KV head ("window-summed importance");
+  * scores are smoothed by a 1-D stride-1 same-length pool (max by default,
+    window clipped at the edges) before ranking;
+  * TopK ranks larger scores first, equal scores by lower position, and the
+    kept history positions are emitted in ascending order, followed by the
+    window (Concat(H', W));
+  * history budget C_H = C - w is clamped to [0, m]: the window is always kept.
+
+Inputs are fp32 arrays or uint16 arrays holding bfloat16 bit patterns; both are
+widened exactly to float64.  Outputs K/V rows are bit copies in the input dtype.
+"""
+
+import math
+
+import numpy as np
+
+POOL_NONE = 0
+POOL_MAX = 1
+POOL_AVG = 2
+
+
+def bf16_bits_to_f64(a):
+    """Exact widening of bfloat16 bit patterns (uint16) or fp32 values to float64."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if a.dtype == np.float32 or a.dtype == np.float64:
+        return a.astype(np.float64)
+    raise TypeError("expected float32 or uint16 (bf16 bits), got %s" % a.dtype)
+
+
+def window_importance(q_group, k_hist):
+    """Window-summed softmax importance of every history key (Eq. 2-4, Eq. 7).
+
+    q_group: [G, w, d] window queries of the G query heads sharing this KV head.
+    k_hist : [m, d]    history keys.
+    Returns I[m] = sum over the G*w query rows of softmax_j(q . k_j / sqrt(d)).
+    """
+    q = bf16_bits_to_f64(q_group)
+    k = bf16_bits_to_f64(k_hist)
+    d = q.shape[-1]
+    rows = q.reshape(-1, d)
+    s = (rows @ k.T) / math.sqrt(d)               # Eq. (3)
+    s = s - s.max(axis=1, keepdims=True)          # shift does not change Eq. (4)
+    e = np.exp(s)
+    p = e / e.sum(axis=1, keepdims=True)          # Eq. (4) over the m history keys
+    return p.sum(axis=0)
+
+
+def pool_1d(x, kernel, mode=POOL_MAX):
+    """Stride-1 same-length 1-D pooling of a score vector (odd kernel).
+
+    MAX: out[j] = max(x[j-r .. j+r]) with the window clipped to [0, m).
+    AVG: out[j] = sum(x[j-r .. j+r], zeros outside) / kernel.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    if mode == POOL_NONE or kernel == 1:
+        return x.copy()
+    if kernel < 1 or kernel % 2 == 0:
+        raise ValueError("pool kernel must be odd and >= 1")
+    r = kernel // 2
+    if mode == POOL_MAX:
+        padded = np.pad(x, r, constant_values=-np.inf)   # clipped window == -inf padding
+        return np.lib.stride_tricks.sliding_window_view(padded, kernel).max(axis=-1)
+    if mode == POOL_AVG:
+        padded = np.pad(x, r, constant_values=0.0)
+        return np.lib.stride_tricks.sliding_window_view(padded, kernel).sum(axis=-1) / kernel
+    raise ValueError("unknown pool mode")
+
+
+def select_topk(scores, k):
+    """Positions of the k largest scores; ties to the lower position; ascending.
+
+    Returns (idx, tau) with tau the k-th largest score (None when k == 0).
+    """
+    scores = np.asarray(scores, dtype=np.float64)
+    m = scores.shape[0]
+    if not 0 <= k <= m:
+        raise ValueError("k out of range")
+    if k == 0:
+        return np.empty(0, dtype=np.int64), None
+    order = np.argsort(-scores, kind="stable")     # equal scores keep ascending position
+    top = order[:k]
+    tau = float(scores[top[-1]])
+    return np.sort(top).astype(np.int64), tau
+
+
+def kept_count(n, w, cap):
+    """Rows kept for a segment of n tokens, window w, capacity cap (Algorithm 3)."""
+    if n <= w or n <= cap:
+        return n
+    return max(cap, w)
+
+
+def compress_segment(q_group, k_seg, v_seg, w, cap, pool_kernel=7, pool_mode=POOL_MAX):
+    """Algorithm 3 for one sequence and one KV head.
+
+    q_group: [G, w, d]; k_seg, v_seg: [n, d]; cap: the head's capacity C.
+    Returns a dict: kept_idx (int64, ascending history then window), k_out,
+    v_out (bit copies), importance, pooled (None on the early-out path), tau, k.
+    """
+    n = k_seg.shape[0]
+    if n <= w or n <= cap:                         # length within capacity: keep all
+        idx = np.arange(n, dtype=np.int64)
+        return dict(kept_idx=idx, k_out=k_seg[idx].copy(), v_out=v_seg[idx].copy(),
+                    importance=None, pooled=None, tau=None, k=None)
+    m = n - w                                      # history / window split
+    k_keep = min(max(cap - w, 0), m)               # C_H = C - window, clamped
+    imp = window_importance(q_group, k_seg[:m])
+    pooled = pool_1d(imp, pool_kernel, pool_mode)
+    hist_idx, tau = select_topk(pooled, k_keep)
+    idx = np.concatenate([hist_idx, np.arange(m, n, dtype=np.int64)])
+    return dict(kept_idx=idx, k_out=k_seg[idx].copy(), v_out=v_seg[idx].copy(),
+                importance=imp, pooled=pooled, tau=tau, k=k_keep)
+
+
+def compress_layer(qwin, k, v, cu_seqlens, budgets, w, pool_kernel=7, pool_mode=POOL_MAX):
+    """One layer over a ragged batch.
+
+    qwin: [B, Hq, w, d]; k, v: [Hkv, T, d] with sequences packed along T at
+    cu_seqlens[B+1]; budgets: [Hkv] capacities of this layer.
+    Returns dict: segments (list over b*Hkv+h of compress_segment results),
+    out_offsets (int64 [B*Hkv+1]), k_out, v_out ([total_kept, d] packed).
+    """
+    qwin = np.asarray(qwin)
+    B, Hq = qwin.shape[0], qwin.shape[1]
+    Hkv = k.shape[0]
+    G = Hq // Hkv
+    segs = []
+    offs = [0]
+    for b in range(B):
+        t0, t1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        for h in range(Hkv):
+            r = compress_segment(qwin[b, h * G:(h + 1) * G], k[h, t0:t1], v[h, t0:t1],
+                                 w, int(budgets[h]), pool_kernel, pool_mode)
+            segs.append(r)
+            offs.append(offs[-1] + r["kept_idx"].shape[0])
+    k_out = np.concatenate([s["k_out"] for s in segs], axis=0)
+    v_out = np.concatenate([s["v_out"] for s in segs], axis=0)
+    return dict(segments=segs, out_offsets=np.asarray(offs, dtype=np.int64),
+                k_out=k_out, v_out=v_out)

@@ -1,0 +1,219 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module only draws random tensors; it holds none of the compression
+method's arithmetic, so both the GPU library's tests and the CPU oracle can be
+fed from it without sharing any of the computation under test.
+
+Shapes follow the Llama-3-8B-Instruct setting of the paper (32 layers x 32
+query heads, 8 KV heads, head_dim 128; Section 4 and Figure 2), prefix lengths
+span its benchmarks (1k-18k for LongBench, up to 129k for LongBench v2), KV
+sizes 64..1024 follow Appendix H, and the INF_sc maps copy the skew of Figures
+4 and 8 (a few high heads, most near zero, layer 1 very low).  The real
+datasets, prompts and model weights are not used anywhere.
+
+All generators use numpy's Philox bit generator; seeds are BASE_SEED + config
+(+ layer).  bfloat16 tensors are produced on the host by round-to-nearest-even
+from fp32 and returned as uint16 bit patterns.
+"""
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+BASE_SEED = 20250815
+
+
+def _rng(*key):
+    ss = np.random.SeedSequence([int(k) for k in key])
+    return np.random.Generator(np.random.Philox(ss))
+
+
+def to_bf16_bits(x):
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = u + np.uint32(0x7FFF) + lsb
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b):
+    return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+@dataclass
+class LayerInputs:
+    """One layer's inputs for the compression pass.
+
+    qwin [B, Hq, w, d]; k, v [Hkv, T, d] (sequences packed along T);
+    cu_seqlens [B+1] int64.  dtype "f32" (float32 arrays) or "bf16" (uint16 bit
+    patterns)."""
+    dtype: str
+    B: int
+    Hq: int
+    Hkv: int
+    d: int
+    w: int
+    cu_seqlens: np.ndarray
+    qwin: np.ndarray
+    k: np.ndarray
+    v: np.ndarray
+    meta: dict = field(default_factory=dict)
+
+
+def make_layer(seed_key, seqlens, Hq, Hkv, d, w, dtype="bf16", bias_frac=0.0, bias_sigma=4.0):
+    """Q/K/V ~ N(0,1).  With bias_frac > 0 that fraction of each sequence's
+    history positions (per KV head, drawn without replacement) has its key
+    shifted by bias_sigma times the unit vector of one random window query of a
+    random query head in the group, which raises that query's logit by about
+    bias_sigma and makes the position stand out."""
+    rng = _rng(*seed_key)
+    seqlens = [int(s) for s in seqlens]
+    B = len(seqlens)
+    cu = np.zeros(B + 1, dtype=np.int64)
+    cu[1:] = np.cumsum(seqlens)
+    T = int(cu[-1])
+    G = Hq // Hkv
+    q = rng.standard_normal((B, Hq, w, d), dtype=np.float32)
+    k = rng.standard_normal((Hkv, T, d), dtype=np.float32)
+    v = rng.standard_normal((Hkv, T, d), dtype=np.float32)
+    if bias_frac > 0.0:
+        for b in range(B):
+            m = seqlens[b] - w
+            if m <= 0:
+                continue
+            cnt = int(round(bias_frac * m))
+            for h in range(Hkv):
+                pos = rng.choice(m, size=cnt, replace=False)
+                qh = rng.integers(0, G, size=cnt) + h * G
+                qi = rng.integers(0, w, size=cnt)
+                qv = q[b, qh, qi, :]
+                qv = qv / np.linalg.norm(qv, axis=1, keepdims=True)
+                k[h, cu[b] + pos, :] += np.float32(bias_sigma) * qv
+    if dtype == "bf16":
+        q, k, v = to_bf16_bits(q), to_bf16_bits(k), to_bf16_bits(v)
+    elif dtype != "f32":
+        raise ValueError("dtype must be 'f32' or 'bf16'")
+    return LayerInputs(dtype, B, Hq, Hkv, d, w, cu, q, k, v)
+
+
+# ---------------------------------------------------------------- INF_sc maps
+
+def inf_uniform(seed_key, L, Hq):
+    return _rng(*seed_key).uniform(0.0, 1.0, size=(L, Hq))
+
+
+def inf_beta(seed_key, L, Hq, a=0.5, b=5.0):
+    return _rng(*seed_key).beta(a, b, size=(L, Hq))
+
+
+def inf_spiky(seed_key, L=32, Hq=32, spike_frac=0.02, low_layer=1, low_scale=0.05):
+    """98% of the cells near zero, U(0, 0.02); 2% spikes, U(0.6, 0.9), at seeded
+    cells; one layer (layer 1 by default) scaled down to be very low."""
+    rng = _rng(*seed_key)
+    m = rng.uniform(0.0, 0.02, size=(L, Hq))
+    n_spike = int(round(spike_frac * L * Hq))
+    cells = rng.choice(L * Hq, size=n_spike, replace=False)
+    m.reshape(-1)[cells] = rng.uniform(0.6, 0.9, size=n_spike)
+    if 0 <= low_layer < L:
+        m[low_layer] *= low_scale
+    return m
+
+
+# ---------------------------------------------------------------- the five configurations
+
+def config1():
+    """Tiny fp32 layer: 4 query / 4 KV heads, d 64, n 1024, w 32, pool 7,
+    average budget 128 (fixed 32), INF_sc ~ U(0,1)."""
+    seed = BASE_SEED + 1
+    lay = make_layer((seed, 0), [1024], 4, 4, 64, 32, dtype="f32")
+    lay.meta = dict(name="c1", avg=128, fixed=32, pool=7, inf=inf_uniform((seed, 1), 1, 4))
+    return lay
+
+
+def config2():
+    """One Llama-3-8B-shaped bf16 layer: 32q/8kv, d 128, n 8192, w 32, 2% biased
+    keys, average budget 128 (fixed 32), INF_sc ~ Beta(0.5, 5)."""
+    seed = BASE_SEED + 2
+    lay = make_layer((seed, 0), [8192], 32, 8, 128, 32, dtype="bf16", bias_frac=0.02)
+    lay.meta = dict(name="c2", avg=128, fixed=32, pool=7, inf=inf_beta((seed, 1), 1, 32))
+    return lay
+
+
+C3_BUDGETS = (64, 256, 1024)
+
+
+def config3_inf():
+    return inf_spiky((BASE_SEED + 3, 1000), 32, 32)
+
+
+def config3_layer(layer, n=32768):
+    """Layer `layer` of the 32-layer prefill: 32q/8kv, d 128, n 32768, w 64,
+    2% biased keys.  Budgets: average 64 / 256 / 1024, fixed 16, from
+    config3_inf()."""
+    seed = BASE_SEED + 3
+    lay = make_layer((seed, layer), [n], 32, 8, 128, 64, dtype="bf16", bias_frac=0.02)
+    lay.meta = dict(name="c3", layer=layer, fixed=16, pool=7)
+    return lay
+
+
+def config5(seqlens=(131072, 65536, 100000, 20000)):
+    """Ragged long-context batch, bf16, 32q/8kv, d 128, w 64, average budget 512
+    (fixed 64); budgets come from config 3's map (the caller picks the row of
+    the lowest layer >= 2 that holds a spike)."""
+    seed = BASE_SEED + 5
+    lay = make_layer((seed, 0), list(seqlens), 32, 8, 128, 64, dtype="bf16", bias_frac=0.02)
+    lay.meta = dict(name="c5", avg=512, fixed=64, pool=7)
+    return lay
+
+
+def config5_layer_row(inf_map, threshold=0.5):
+    """Index of the lowest layer >= 2 whose row holds a spike (> threshold)."""
+    for l in range(2, inf_map.shape[0]):
+        if (inf_map[l] > threshold).any():
+            return l
+    return 2
+
+
+# ---------------------------------------------------------------- Stage 1 rows (configuration 4)
+
+@dataclass
+class NeedleRows:
+    """rows [L, H, T, n] fp32 attention rows; the needle occupies
+    [needle_start, needle_start + needle_len); token_ids is bookkeeping only."""
+    rows: np.ndarray
+    needle_start: int
+    needle_len: int
+    topk: int
+    token_ids: np.ndarray
+
+
+def config4(L=32, H=32, T=16, n=16384, needle_len=32, vocab=128000, seed_extra=0):
+    """Synthetic needle-in-a-haystack decode rows.  Each row is softmax(z),
+    z ~ N(0,1).  With probability 0.005 the row is a "surface" row (z at the
+    needle token being emitted, start + t, raised by 12); with probability
+    0.015 it is a "logic" row (z raised by 6 on 8 positions drawn from the
+    needle's other tokens and the 16 tokens on either side); otherwise it stays
+    diffuse."""
+    seed = BASE_SEED + 4
+    rng = _rng(seed, seed_extra)
+    token_ids = rng.integers(0, vocab, size=n, dtype=np.int64)
+    start = int(rng.integers(0, n - needle_len + 1))
+    rows = np.empty((L, H, T, n), dtype=np.float32)
+    for l in range(L):
+        z = rng.standard_normal((H, T, n), dtype=np.float32)
+        kind = rng.random((H, T))
+        for h in range(H):
+            for t in range(T):
+                if kind[h, t] < 0.005:
+                    z[h, t, start + (t % needle_len)] += np.float32(12.0)
+                elif kind[h, t] < 0.020:
+                    lo = max(0, start - 16)
+                    hi = min(n, start + needle_len + 16)
+                    cand = np.array([p for p in range(lo, hi) if p != start + (t % needle_len)])
+                    pos = rng.choice(cand, size=min(8, cand.shape[0]), replace=False)
+                    z[h, t, pos] += np.float32(6.0)
+        z64 = z.astype(np.float64)
+        z64 -= z64.max(axis=-1, keepdims=True)
+        e = np.exp(z64)
+        rows[l] = (e / e.sum(axis=-1, keepdims=True)).astype(np.float32)
+    return NeedleRows(rows, start, needle_len, needle_len, token_ids)
