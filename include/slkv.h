@@ -1,0 +1,164 @@
+/*
+ * slkv.h - C ABI of the SurfaceLogicKV prefill KV-compression pass for AMD MI355X (gfx950).
+ *
+ * The paper (arXiv 2508.15806) defines a two-stage method:
+ *   Stage 1 (Section 3.2, Algorithm 1): per attention head, count how the attention mass of
+ *     decode rows over a needle-in-a-haystack prompt splits into correct / distracted /
+ *     subconscious weight and form SF_sc, LG_sc and INF_sc          -> slkv_score_heads
+ *   Stage 2a (Section 3.3, Eq. 6, Algorithm 2): turn the INF_sc map into one integer KV
+ *     capacity per (layer, head): a fixed part plus a share of a dynamic pool
+ *                                                                    -> slkv_allocate_budgets
+ *   Stage 2b (Section 3.4, Eq. 7-8, Algorithm 3): at prefill, per layer and head, score the
+ *     history keys against the last window of queries, keep the top-ranked history entries
+ *     within the capacity plus the whole window                      -> slkv_compress_layer
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every
+ *     buffer; the library allocates no device memory and keeps no state between calls.
+ *   - slkv_score_heads and slkv_compress_layer only enqueue work on `hip_stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream) and return without
+ *     synchronising.  Host-side descriptors are consumed before the call returns.
+ *   - Every argument is validated before the first GPU call; on any error nothing is
+ *     enqueued and no output is written.  slkv_last_error() gives a detail string for the
+ *     calling thread.
+ *   - Device pointers must be 16-byte aligned.
+ */
+#ifndef SLKV_H
+#define SLKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SLKV_OK = 0,
+  SLKV_ERR_NULL = 1,        /* a required pointer is NULL */
+  SLKV_ERR_BAD_ARG = 2,     /* a size / count / stride / alignment is invalid */
+  SLKV_ERR_BAD_VALUE = 3,   /* host data out of range (INF_sc not in [0,1], NaN, ...) */
+  SLKV_ERR_UNSUPPORTED = 4, /* valid but outside what the kernels cover (head_dim, rows) */
+  SLKV_ERR_WORKSPACE = 5,   /* workspace smaller than slkv_workspace_bytes() */
+  SLKV_ERR_CAPACITY = 6,    /* output buffers smaller than slkv_compacted_sizes() */
+  SLKV_ERR_HIP = 7          /* a HIP call failed (kernel launch) */
+} slkv_status;
+
+typedef enum { SLKV_F32 = 0, SLKV_BF16 = 1 } slkv_dtype;
+typedef enum { SLKV_POOL_NONE = 0, SLKV_POOL_MAX = 1, SLKV_POOL_AVG = 2 } slkv_pool;
+typedef enum { SLKV_BUDGET_EXACT = 0, SLKV_BUDGET_PAPER_LITERAL = 1 } slkv_budget_mode;
+
+/* Static description of a status code. */
+const char* slkv_status_str(slkv_status s);
+/* Detail of the last error on the calling thread; valid until its next slkv call. */
+const char* slkv_last_error(void);
+/* ABI version: major * 1000 + minor. */
+int32_t slkv_version(void);
+
+/* ------------------------------------------------------------------ Stage 1 -----------
+ * Algorithm 1 (Section 3.2).  For every row W (length n) of every head: T_k = the `topk`
+ * largest weights (equal weights rank by lower position),
+ *   WO = sum of W over needle and T_k, WD = sum of W over T_k outside the needle,
+ *   TNW = sum of W over the needle, WS = max(0, TNW - WO), Wide = sum(W) - WO - WD - WS.
+ * The five accumulators of head (l,h) are increased by the sums over its T rows, so several
+ * calls (other prompts, depths, lengths) accumulate into the same d_acc.  If d_scores is not
+ * NULL it receives, from the updated accumulators,
+ *   SF = WO/(WO+WD), LG = WO/(WO+WS), INF = 2 SF LG/(SF+LG)   (0/0 = 0).
+ *
+ * d_rows    [L][H][T][n] fp32, rows contiguous (device, read only)
+ * needle    [needle_start, needle_start + needle_len) inside [0, n), the same for all rows
+ * topk      1..n
+ * d_acc     [L][H][5] double, in/out: sum WO, sum WD, sum WS, sum Wide, row count.  The
+ *           caller zeroes it before the first call.
+ * d_scores  [L][H][3] double out, may be NULL
+ * d_workspace / workspace_bytes: at least slkv_score_heads_workspace_bytes(L,H,T,n) bytes
+ * Errors: NULL, BAD_ARG (sizes, needle, topk, alignment), WORKSPACE, HIP.
+ */
+slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t H, int32_t T, int64_t n,
+                             int64_t needle_start, int32_t needle_len, int32_t topk,
+                             double* d_acc, double* d_scores,
+                             void* d_workspace, size_t workspace_bytes, void* hip_stream);
+size_t slkv_score_heads_workspace_bytes(int32_t L, int32_t H, int32_t T, int64_t n);
+
+/* ------------------------------------------------------------------ Stage 2a ----------
+ * Eq. (6) / Algorithm 2.  Pure host code, no GPU call.
+ *
+ * h_inf      [L][Hq] INF_sc per query head, each finite and in [0, 1]
+ * Hkv        KV heads per layer; Hq % Hkv == 0.  The INF_sc of the Hq/Hkv query heads that
+ *            share a KV head are averaged first; capacities are per KV head.
+ * avg_budget average capacity per KV head (b_c); fixed_budget the fixed part b_c(1 - 1/beta),
+ *            0 <= fixed <= avg.
+ * mode       SLKV_BUDGET_EXACT: a layer's share of the dynamic pool (avg-fixed)*L*Hkv is
+ *              proportional to 0.01 + (layer INF sum / total INF sum), a head's share inside
+ *              its layer is proportional to its INF_sc; both splits use the largest-remainder
+ *              rule on exact integers (INF_sc quantised to 2^-30), so the capacities are
+ *              integers >= fixed that sum to avg*L*Hkv exactly.
+ *            SLKV_BUDGET_PAPER_LITERAL: Algorithm 2 as printed (global normalisation, the 0.01
+ *              offset not renormalised, each head rounded half up on its own); does not sum
+ *              to the total.
+ * h_budgets  [L][Hkv] out.
+ * Errors: NULL, BAD_ARG (sizes, Hq % Hkv, fixed > avg, overflow), BAD_VALUE (INF_sc).
+ */
+slkv_status slkv_allocate_budgets(const double* h_inf, int32_t L, int32_t Hq, int32_t Hkv,
+                                  int32_t avg_budget, int32_t fixed_budget, int32_t mode,
+                                  int32_t* h_budgets);
+/* floor(avg * (1 - 1/beta) + 0.5): the fixed part of Algorithm 2 for a ratio beta >= 1. */
+int32_t slkv_fixed_from_beta(int32_t avg_budget, double beta);
+
+/* ------------------------------------------------------------------ Stage 2b ----------
+ * Algorithm 3 for one layer over a ragged batch of B sequences.
+ * Sequence b has n_b = cu_seqlens[b+1] - cu_seqlens[b] tokens; its last w tokens are the
+ * observation window, the first m_b = n_b - w its history.  For KV head h with capacity C_h:
+ *   n_b <= C_h or n_b <= w : every token is kept;
+ *   otherwise k = min(max(C_h - w, 0), m_b) history tokens are kept, those with the largest
+ *   pooled importance (equal scores rank by lower position), followed by the window.
+ * importance[j] = sum over the G = Hq/Hkv query heads of the group and the w window queries of
+ *   softmax_j(q . k_j / sqrt(d)) with the softmax over the m_b history keys only;
+ * pooled = stride-1 same-length pool of width pool_kernel over importance (max: window clipped
+ *   at the ends; avg: zeros outside, divided by pool_kernel).
+ * Kept rows of K and V are copied bit for bit, history positions ascending then the window.
+ */
+typedef struct {
+  uint32_t struct_size;       /* sizeof(slkv_layer_desc) */
+  int32_t dtype;              /* slkv_dtype of Q, K, V */
+  int32_t B, Hq, Hkv, d, w;   /* d in {64, 128}; w >= 1; Hq % Hkv == 0; (Hq/Hkv)*w <= 512 */
+  int32_t pool_kernel;        /* odd, 1..63; 1 = no pooling */
+  int32_t pool;               /* slkv_pool */
+  int32_t reserved;           /* 0 */
+  const int64_t* h_cu_seqlens; /* [B+1] host: token offsets into the packed K/V, non-decreasing,
+                                  cu[0] >= 0, cu[B] < 2^31 */
+  int64_t k_stride_tok, k_stride_head; /* elements between tokens / KV heads of d_k; rows of d
+                                          elements are contiguous; both multiples of 8 */
+  int64_t v_stride_tok, v_stride_head; /* same for d_v */
+  const int32_t* h_budgets;   /* [Hkv] host: this layer's capacities C_h >= 0 */
+} slkv_layer_desc;
+
+/* Kept-row counts.  h_out_offsets[B*Hkv+1] (host, may be NULL) receives the exclusive scan of
+ * the kept counts in segment order s = b*Hkv + h; *total_kept (may be NULL) their sum. */
+slkv_status slkv_compacted_sizes(const slkv_layer_desc* desc, int64_t* h_out_offsets,
+                                 int64_t* total_kept);
+/* Device workspace slkv_compress_layer needs for this descriptor. */
+slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes);
+
+/* d_qwin   [B][Hq][w][d] window queries (device, read only)
+ * d_k, d_v packed keys / values: element (h, t, :) at h*stride_head + t*stride_tok
+ * d_k_out, d_v_out [total_kept][d] out, segment s at row h_out_offsets[s]
+ * d_kept_idx [total_kept] int32 out: kept positions inside the sequence, per segment
+ * d_out_offsets [B*Hkv+1] int64 out, may be NULL: device copy of the offsets
+ * d_importance, d_pooled: may be NULL.  fp32 [Hkv * cu[B]] each; segment (b,h) occupies
+ *          m_b entries starting at Hkv*cu[b] + h*n_b and is written only when the segment is
+ *          actually ranked (n_b > max(C_h, w) and 0 < k < m_b).
+ * out_capacity_rows: rows available in d_k_out / d_v_out / d_kept_idx
+ * Errors: NULL, BAD_ARG, UNSUPPORTED, WORKSPACE, CAPACITY, HIP.
+ */
+slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin,
+                                const void* d_k, const void* d_v,
+                                void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                int64_t* d_out_offsets, float* d_importance, float* d_pooled,
+                                int64_t out_capacity_rows,
+                                void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLKV_H */

@@ -1,0 +1,60 @@
+"""Convenience layer over binding.py: uploads host arrays, allocates outputs and
+workspace with torch, calls the library.  No arithmetic of the method lives here."""
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def to_device(arr, dtype, device="cuda"):
+    """numpy fp32 array, or uint16 array of bfloat16 bit patterns -> device tensor."""
+    if dtype == "bf16":
+        t = torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).to(device)
+        return t.view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
+
+
+def to_host(t):
+    """device tensor -> numpy (bfloat16 comes back as uint16 bit patterns)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class LayerCall:
+    """Device buffers + descriptor for repeated calls on one layer's shapes."""
+
+    def __init__(self, dtype, B_, Hq, Hkv, d, w, cu_seqlens, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX,
+                 device="cuda", debug_scores=False):
+        T = int(cu_seqlens[-1])
+        self.dtype = dtype
+        self.layer = B.Layer(B.SLKV_BF16 if dtype == "bf16" else B.SLKV_F32, B_, Hq, Hkv, d, w, cu_seqlens,
+                             budgets, (d, T * d), (d, T * d), pool_kernel, pool)
+        self.offsets, self.total_kept = B.slkv_compacted_sizes(self.layer)
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        rows = max(self.total_kept, 1)
+        self.k_out = torch.empty((rows, d), dtype=tdt, device=device)
+        self.v_out = torch.empty((rows, d), dtype=tdt, device=device)
+        self.kept_idx = torch.empty((rows,), dtype=torch.int32, device=device)
+        self.out_offsets = torch.empty((B_ * Hkv + 1,), dtype=torch.int64, device=device)
+        self.workspace = torch.empty((B.slkv_workspace_bytes(self.layer),), dtype=torch.uint8, device=device)
+        self.importance = self.pooled = None
+        if debug_scores:
+            self.importance = torch.zeros((max(Hkv * T, 1),), dtype=torch.float32, device=device)
+            self.pooled = torch.zeros((max(Hkv * T, 1),), dtype=torch.float32, device=device)
+
+    def run(self, qwin, k, v, stream=None):
+        B.slkv_compress_layer(self.layer, qwin, k, v, self.k_out, self.v_out, self.kept_idx, self.workspace,
+                              self.out_offsets, self.importance, self.pooled, stream)
+
+
+def score_heads(rows, needle_start, needle_len, topk, acc=None, stream=None):
+    """rows: [L,H,T,n] fp32 device tensor.  Returns (acc [L,H,5], scores [L,H,3]) float64 device tensors."""
+    L, H, T, n = rows.shape
+    if acc is None:
+        acc = torch.zeros((L, H, 5), dtype=torch.float64, device=rows.device)
+    scores = torch.empty((L, H, 3), dtype=torch.float64, device=rows.device)
+    ws = torch.empty((max(B.slkv_score_heads_workspace_bytes(L, H, T, n), 16),), dtype=torch.uint8, device=rows.device)
+    B.slkv_score_heads(rows, needle_start, needle_len, topk, acc, scores, ws, stream)
+    return acc, scores

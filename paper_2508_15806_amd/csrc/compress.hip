@@ -1,0 +1,649 @@
+// Stage 2b of SurfaceLogicKV (Section 3.4, Eq. 7-8, Algorithm 3) on gfx950:
+//   pass 1  score_*<.., 1>  window-query x history-key logits, per-row running max / sum-exp
+//   combine                  per-row log-sum-exp over the key chunks
+//   pass 2  score_*<.., 2>  logits again, exp(logit - lse) summed down the G*w rows -> importance
+//   select                   1-D pooling + per-head top-k (radix select, ordered compaction)
+//   gather                   kept K/V rows -> compacted ragged cache
+// bf16 inputs use the 32x32x16 bf16 MFMA with Q held in registers and K tiles staged in LDS;
+// fp32 inputs use plain FMA kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "device_utils.h"
+#include "slkv_internal.h"
+
+namespace slkv {
+
+// Per-launch table of (sequence, KV head) segments, passed by value as a kernel argument.
+struct SegTable {
+  int32_t nseg;
+  int32_t total_chunks;
+  int32_t tok_begin[kMaxSegPerLaunch];   // first token of the sequence in the packed K/V
+  int32_t n[kMaxSegPerLaunch];           // tokens in the sequence
+  int32_t kkeep[kMaxSegPerLaunch];       // history rows to keep; -1 = keep every token
+  int32_t out_off[kMaxSegPerLaunch + 1]; // first output row of the segment
+  int32_t head[kMaxSegPerLaunch];        // KV head
+  int32_t qrow_off[kMaxSegPerLaunch];    // first row of the segment's [G*w][d] query block
+  int32_t score_off[kMaxSegPerLaunch];   // offset of the segment in the importance / pooled arrays
+  int32_t chunk_begin[kMaxSegPerLaunch + 1];  // prefix of key-chunk counts (0 chunks when not ranked)
+  int32_t seg_global[kMaxSegPerLaunch];  // index b*Hkv + h
+};
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+union Pack16 {
+  uint4 u;
+  bf16x8 b;
+};
+
+__device__ __forceinline__ int find_segment(const int32_t* prefix, int nseg, int x) {
+  // largest s with prefix[s] <= x, prefix non-decreasing, prefix[nseg] > x
+  int lo = 0, hi = nseg - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (prefix[mid] <= x) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Merge two (max, sum) pairs of a running softmax in the log2 domain.
+__device__ __forceinline__ void merge_stats(float& m, float& s, float m2, float s2) {
+  float mn = fmaxf(m, m2);
+  float mu = mn == -INFINITY ? 0.f : mn;
+  s = s * fast_exp2(m - mu) + s2 * fast_exp2(m2 - mu);
+  m = mn;
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA scoring.  One workgroup (4 waves) owns one chunk of history keys of one segment.
+// Wave (rb, ks): rows [rb*32*MT, (rb+1)*32*MT) of the G*w query rows, key sub-tile ks of each
+// LDS tile.  The 32x32x16 MFMA takes, per lane, 8 consecutive k-elements of row (lane%32) at
+// k offset 8*(lane/32) for both operands, and returns for result register i the element at
+// row 8*(i/4) + 4*(lane/32) + i%4, column lane%32.
+//   PASS 1: D[key][qrow]: a lane owns one query row per MFMA tile -> running (max, sum-exp).
+//   PASS 2: D[qrow][key]: a lane owns one key column -> sum over rows of exp2(x - lse[row]).
+template <int DK, int MT, int RB, int PASS>
+__global__ __launch_bounds__(256) void score_bf16_kernel(const SegTable tab, const uint16_t* __restrict__ q,
+                                                         const uint16_t* __restrict__ kmat, int64_t k_stride_tok,
+                                                         int64_t k_stride_head, int R, int Rpad, int w, int CH,
+                                                         float c_log2, float* __restrict__ part,
+                                                         const float* __restrict__ lse, float* __restrict__ imp) {
+  constexpr int KS = 4 / RB;
+  constexpr int TK = 32 * KS;
+  constexpr int KK = DK / 16;
+  constexpr int ROWB = DK * 2 + 16;
+  constexpr int CPR = DK * 2 / 16;
+  constexpr int LPT = (TK * CPR + 255) / 256;
+  __shared__ __attribute__((aligned(16))) unsigned char ktile[2][TK * ROWB];
+  __shared__ float red[2][RB][TK];
+  __shared__ float2 comb[KS][RB * 32 * MT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int rb = wv % RB, ks = wv / RB;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  const int bid = blockIdx.x;
+  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
+  const int chunk = bid - tab.chunk_begin[seg];
+  const int m = tab.n[seg] - w;
+  const int key_begin = chunk * CH;
+  const int key_end = min(m, key_begin + CH);
+  const int ntiles = (key_end - key_begin + TK - 1) / TK;
+  const uint16_t* kbase = kmat + (int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok;
+
+  // query rows of this wave, kept in registers for the whole chunk
+  bf16x8 qreg[MT][KK];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int row = rb * 32 * MT + mt * 32 + l32;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      Pack16 p;
+      p.u = make_uint4(0, 0, 0, 0);
+      if (row < R) p.u = *reinterpret_cast<const uint4*>(q + ((int64_t)tab.qrow_off[seg] + row) * DK + kk * 16 + half * 8);
+      qreg[mt][kk] = p.b;
+    }
+  }
+
+  float lse_r[PASS == 2 ? MT : 1][16];
+  if (PASS == 2) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rb * 32 * MT + mt * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+        lse_r[mt][i] = row < R ? lse[seg * Rpad + row] : INFINITY;
+      }
+  }
+  float m_run[MT], s_run[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    m_run[mt] = -INFINITY;
+    s_run[mt] = 0.f;
+  }
+
+  uint4 pf[LPT];
+  auto load_tile = [&](int t) {
+    const int key0 = key_begin + t * TK;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int idx = i * 256 + tid;
+      const int row = idx / CPR, c = idx % CPR;
+      pf[i] = make_uint4(0, 0, 0, 0);
+      if (idx < TK * CPR && key0 + row < key_end)
+        pf[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)(key0 + row) * k_stride_tok + c * 8);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int idx = i * 256 + tid;
+      const int row = idx / CPR, c = idx % CPR;
+      if (idx < TK * CPR) *reinterpret_cast<uint4*>(&ktile[buf][row * ROWB + c * 16]) = pf[i];
+    }
+  };
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < ntiles) load_tile(t + 1);
+
+    bf16x8 kreg[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      Pack16 p;
+      p.u = *reinterpret_cast<const uint4*>(&ktile[buf][(ks * 32 + l32) * ROWB + kk * 32 + half * 16]);
+      kreg[kk] = p.b;
+    }
+    const int key0 = key_begin + t * TK + ks * 32;   // first key of this wave's sub-tile
+    float colsum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      f32x16 acc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        if (PASS == 1)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk], qreg[mt][kk], acc, 0, 0, 0);
+        else
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[mt][kk], kreg[kk], acc, 0, 0, 0);
+      }
+      if (PASS == 1) {
+        // lane: query row mt*32 + l32, keys key0 + 8*(i/4) + 4*half + i%4
+        if (key0 + 32 > key_end) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (key0 + 8 * (i >> 2) + 4 * half + (i & 3) >= key_end) acc[i] = -INFINITY;
+        }
+        float mx = acc[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, acc[i]);
+        const float mn = fmaxf(m_run[mt], mx * c_log2);
+        const float mu = mn == -INFINITY ? 0.f : mn;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c_log2, -mu));
+        s_run[mt] = s_run[mt] * fast_exp2(m_run[mt] - mu) + sum;
+        m_run[mt] = mn;
+      } else {
+        // lane: key key0 + l32, query rows mt*32 + 8*(i/4) + 4*half + i%4
+#pragma unroll
+        for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], c_log2, -lse_r[mt][i]));
+      }
+    }
+    if (PASS == 2) {
+      colsum += __shfl_xor(colsum, 32, 64);
+      if (half == 0) red[buf][rb][ks * 32 + l32] = colsum;
+    }
+    if (t + 1 < ntiles) store_tile(buf ^ 1);
+    __syncthreads();
+    if (PASS == 2) {
+      if (tid < TK) {
+        float v = 0.f;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) v += red[buf][r][tid];
+        const int key = key_begin + t * TK + tid;
+        if (key < key_end) imp[tab.score_off[seg] + key] = v;
+      }
+    }
+  }
+
+  if (PASS == 1) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float m2 = __shfl_xor(m_run[mt], 32, 64);
+      float s2 = __shfl_xor(s_run[mt], 32, 64);
+      merge_stats(m_run[mt], s_run[mt], m2, s2);
+      if (half == 0) comb[ks][rb * 32 * MT + mt * 32 + l32] = make_float2(m_run[mt], s_run[mt]);
+    }
+    __syncthreads();
+    for (int row = tid; row < RB * 32 * MT; row += 256) {
+      float mm = comb[0][row].x, ss = comb[0][row].y;
+#pragma unroll
+      for (int k2 = 1; k2 < KS; ++k2) merge_stats(mm, ss, comb[k2][row].x, comb[k2][row].y);
+      if (row < Rpad) {
+        part[((int64_t)bid * Rpad + row) * 2 + 0] = mm;
+        part[((int64_t)bid * Rpad + row) * 2 + 1] = ss;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 scoring with plain FMAs (small shapes).  Same chunking and outputs as the bf16 kernels.
+// PASS 1: thread = query row, K tile in LDS (broadcast reads).  PASS 2: thread = key, Q rows in LDS.
+template <int DK, int PASS>
+__global__ __launch_bounds__(256) void score_f32_kernel(const SegTable tab, const float* __restrict__ q,
+                                                        const float* __restrict__ kmat, int64_t k_stride_tok,
+                                                        int64_t k_stride_head, int R, int Rpad, int w, int CH,
+                                                        float c_log2, float* __restrict__ part,
+                                                        const float* __restrict__ lse, float* __restrict__ imp) {
+  constexpr int TROWS = 32;
+  __shared__ __attribute__((aligned(16))) float tile[TROWS][DK];
+  __shared__ float lse_s[TROWS];
+  const int tid = threadIdx.x;
+  const int bid = blockIdx.x;
+  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
+  const int chunk = bid - tab.chunk_begin[seg];
+  const int m = tab.n[seg] - w;
+  const int key_begin = chunk * CH;
+  const int key_end = min(m, key_begin + CH);
+  const float* kbase = kmat + (int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok;
+  const float* qbase = q + (int64_t)tab.qrow_off[seg] * DK;
+
+  if (PASS == 1) {
+    for (int r0 = 0; r0 < R; r0 += 256) {
+      const int row = r0 + tid;
+      float qr[DK];
+#pragma unroll
+      for (int p = 0; p < DK; ++p) qr[p] = row < R ? qbase[(int64_t)row * DK + p] : 0.f;
+      float mm = -INFINITY, ss = 0.f;
+      for (int k0 = key_begin; k0 < key_end; k0 += TROWS) {
+        __syncthreads();
+        for (int idx = tid; idx < TROWS * DK; idx += 256) {
+          const int kr = idx / DK, p = idx % DK;
+          tile[kr][p] = k0 + kr < key_end ? kbase[(int64_t)(k0 + kr) * k_stride_tok + p] : 0.f;
+        }
+        __syncthreads();
+        const int cnt = min(TROWS, key_end - k0);
+        for (int kr = 0; kr < cnt; ++kr) {
+          float acc = 0.f;
+#pragma unroll
+          for (int p = 0; p < DK; ++p) acc = fmaf(qr[p], tile[kr][p], acc);
+          merge_stats(mm, ss, acc * c_log2, 1.f);
+        }
+      }
+      if (row < Rpad) {
+        part[((int64_t)bid * Rpad + row) * 2 + 0] = row < R ? mm : -INFINITY;
+        part[((int64_t)bid * Rpad + row) * 2 + 1] = row < R ? ss : 0.f;
+      }
+    }
+  } else {
+    for (int k0 = key_begin; k0 < key_end; k0 += 256) {
+      const int key = k0 + tid;
+      float kr[DK];
+#pragma unroll
+      for (int p = 0; p < DK; ++p) kr[p] = key < key_end ? kbase[(int64_t)key * k_stride_tok + p] : 0.f;
+      float colsum = 0.f;
+      for (int r0 = 0; r0 < R; r0 += TROWS) {
+        __syncthreads();
+        for (int idx = tid; idx < TROWS * DK; idx += 256) {
+          const int rr = idx / DK, p = idx % DK;
+          tile[rr][p] = r0 + rr < R ? qbase[(int64_t)(r0 + rr) * DK + p] : 0.f;
+        }
+        if (tid < TROWS) lse_s[tid] = r0 + tid < R ? lse[seg * Rpad + r0 + tid] : INFINITY;
+        __syncthreads();
+        const int cnt = min(TROWS, R - r0);
+        for (int rr = 0; rr < cnt; ++rr) {
+          float acc = 0.f;
+#pragma unroll
+          for (int p = 0; p < DK; ++p) acc = fmaf(tile[rr][p], kr[p], acc);
+          colsum += fast_exp2(fmaf(acc, c_log2, -lse_s[rr]));
+        }
+      }
+      if (key < key_end) imp[tab.score_off[seg] + key] = colsum;
+    }
+  }
+}
+
+// Per-row log-sum-exp (log2 domain) over a segment's chunks, chunks taken in order.
+__global__ __launch_bounds__(256) void combine_kernel(const SegTable tab, int Rpad, const float* __restrict__ part,
+                                                      float* __restrict__ lse) {
+  const int seg = blockIdx.x;
+  const int c0 = tab.chunk_begin[seg], c1 = tab.chunk_begin[seg + 1];
+  if (c0 == c1) return;
+  for (int row = threadIdx.x; row < Rpad; row += 256) {
+    float mm = -INFINITY, ss = 0.f;
+    for (int c = c0; c < c1; ++c)
+      merge_stats(mm, ss, part[((int64_t)c * Rpad + row) * 2], part[((int64_t)c * Rpad + row) * 2 + 1]);
+    lse[seg * Rpad + row] = ss > 0.f ? mm + log2f(ss) : INFINITY;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Pooling + top-k of one segment per workgroup (Algorithm 3, steps 7-8).  Writes the kept
+// positions: history positions ascending, then the window.
+constexpr int kSelThreads = 1024;
+
+__device__ __forceinline__ float pooled_at(const float* __restrict__ I, int j, int m, int radius, int mode, float inv_p) {
+  if (mode == SLKV_POOL_NONE || radius == 0) return I[j];
+  const int lo = max(0, j - radius), hi = min(m - 1, j + radius);
+  if (mode == SLKV_POOL_MAX) {
+    float v = I[lo];
+    for (int t = lo + 1; t <= hi; ++t) v = fmaxf(v, I[t]);
+    return v;
+  }
+  float v = 0.f;
+  for (int t = lo; t <= hi; ++t) v += I[t];
+  return v * inv_p;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab, int w, int pool_kernel, int pool_mode,
+                                                             const float* __restrict__ imp, float* __restrict__ pooled,
+                                                             int32_t* __restrict__ kept_idx,
+                                                             int64_t* __restrict__ d_out_offsets, int is_last_group) {
+  constexpr int NT = kSelThreads;
+  constexpr int NW = NT / 64;
+  constexpr int SUPER = 128;                       // tiles of NT elements per compaction round
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t sh_scan[NW];
+  __shared__ uint32_t res[2];
+  __shared__ unsigned long long cnt[SUPER * NW];
+  __shared__ unsigned long long sh_scan64[NW];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int seg = blockIdx.x;
+  const int n = tab.n[seg];
+  const int kk = tab.kkeep[seg];
+  int32_t* out = kept_idx + tab.out_off[seg];
+  if (d_out_offsets && tid == 0) {
+    d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
+    if (is_last_group && seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
+  }
+  if (kk < 0) {                                    // whole segment kept
+    for (int j = tid; j < n; j += NT) out[j] = j;
+    return;
+  }
+  const int m = n - w;
+  for (int j = tid; j < w; j += NT) out[kk + j] = m + j;
+  if (kk == 0) return;
+  if (kk >= m) {
+    for (int j = tid; j < m; j += NT) out[j] = j;
+    return;
+  }
+  const float* I = imp + tab.score_off[seg];
+  float* P = pooled + tab.score_off[seg];
+  const int radius = pool_kernel / 2;
+  const float inv_p = 1.f / (float)pool_kernel;
+  for (int j = tid; j < m; j += NT) P[j] = pooled_at(I, j, m, radius, pool_mode, inv_p);
+  // each thread re-reads only what it wrote itself (same j -> thread map in every sweep)
+  uint32_t need_eq;
+  auto key_at = [&](int64_t j, uint32_t& key) {
+    key = __float_as_uint(P[j]);                   // scores are >= 0: the bit pattern is monotone
+    return true;
+  };
+  const uint32_t tau = block_radix_select<NT>(key_at, (int64_t)m, (uint32_t)kk, hist, sh_scan, res, &need_eq);
+
+  // ordered compaction: position = (#greater before) + min(#equal before, need_eq)
+  unsigned long long carry = 0;                    // (equal << 32) | greater, over finished rounds
+  for (int base0 = 0; base0 < m; base0 += SUPER * NT) {
+    const int tiles = min(SUPER, (m - base0 + NT - 1) / NT);
+    for (int t = 0; t < tiles; ++t) {
+      const int j = base0 + t * NT + tid;
+      const uint32_t key = j < m ? __float_as_uint(P[j]) : 0u;
+      const unsigned long long bg = __ballot(j < m && key > tau);
+      const unsigned long long be = __ballot(j < m && key == tau);
+      if (lane == 0) cnt[t * NW + wv] = ((unsigned long long)__popcll(be) << 32) | (unsigned long long)__popcll(bg);
+    }
+    __syncthreads();
+    // exclusive scan of cnt[0 .. tiles*NW) in (tile, wave) order, two entries per thread
+    {
+      const int e0 = 2 * tid, e1 = 2 * tid + 1, ne = tiles * NW;
+      const unsigned long long a = e0 < ne ? cnt[e0] : 0ull, b = e1 < ne ? cnt[e1] : 0ull;
+      const unsigned long long incl = block_incl_scan<NT, unsigned long long>(a + b, sh_scan64);
+      if (e0 < ne) cnt[e0] = carry + incl - a - b;
+      if (e1 < ne) cnt[e1] = carry + incl - b;
+      __syncthreads();
+    }
+    unsigned long long last = 0;
+    for (int t = 0; t < tiles; ++t) {
+      const int j = base0 + t * NT + tid;
+      const uint32_t key = j < m ? __float_as_uint(P[j]) : 0u;
+      const bool g = j < m && key > tau, e = j < m && key == tau;
+      const unsigned long long bg = __ballot(g), be = __ballot(e);
+      const unsigned long long lower = (1ull << lane) - 1ull;
+      const unsigned long long basev = cnt[t * NW + wv];
+      const uint32_t g_before = (uint32_t)(basev & 0xffffffffull) + (uint32_t)__popcll(bg & lower);
+      const uint32_t e_before = (uint32_t)(basev >> 32) + (uint32_t)__popcll(be & lower);
+      if (g || (e && e_before < need_eq)) out[g_before + min(e_before, need_eq)] = j;
+      if (t == tiles - 1 && wv == NW - 1)
+        last = basev + (((unsigned long long)__popcll(be) << 32) | (unsigned long long)__popcll(bg));
+    }
+    // totals after this round: value held by the last wave; broadcast through LDS
+    __syncthreads();
+    if (tid == NT - 1) cnt[0] = last;
+    __syncthreads();
+    carry = cnt[0];
+    __syncthreads();
+  }
+}
+
+// Copies kept rows of K and V (bit copies) into the packed output; one 16-byte lane per piece.
+__global__ __launch_bounds__(256) void gather_kernel(const SegTable tab, int lanes_per_row, int elt_bytes,
+                                                     const unsigned char* __restrict__ k,
+                                                     const unsigned char* __restrict__ v, int64_t k_stride_tok,
+                                                     int64_t k_stride_head, int64_t v_stride_tok, int64_t v_stride_head,
+                                                     unsigned char* __restrict__ k_out, unsigned char* __restrict__ v_out,
+                                                     const int32_t* __restrict__ kept_idx) {
+  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t rel = g / lanes_per_row;
+  const int c = (int)(g % lanes_per_row);
+  const int64_t row0 = tab.out_off[0], row1 = tab.out_off[tab.nseg];
+  const int64_t row = row0 + rel;
+  if (row >= row1) return;
+  const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
+  const int64_t tok = (int64_t)tab.tok_begin[seg] + kept_idx[row];
+  const int64_t h = tab.head[seg];
+  const int64_t row_bytes = (int64_t)lanes_per_row * 16;
+  const uint4 kv = *reinterpret_cast<const uint4*>(k + (h * k_stride_head + tok * k_stride_tok) * elt_bytes + c * 16);
+  const uint4 vv = *reinterpret_cast<const uint4*>(v + (h * v_stride_head + tok * v_stride_tok) * elt_bytes + c * 16);
+  *reinterpret_cast<uint4*>(k_out + row * row_bytes + c * 16) = kv;
+  *reinterpret_cast<uint4*>(v_out + row * row_bytes + c * 16) = vv;
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side: planning, validation, launches.
+struct Plan {
+  int R, Rpad, CH;
+  int64_t total_tokens;
+  size_t part_bytes, lse_bytes, score_bytes;
+  size_t off_part, off_lse, off_imp, off_pooled, total_bytes;
+  int groups;
+};
+
+static bool seg_ranked(int64_t n, int64_t w, int64_t cap) { return n > w && n > cap && cap > w; }
+
+static void make_plan(const slkv_layer_desc* d, Plan& p) {
+  p.R = (d->Hq / d->Hkv) * d->w;
+  p.Rpad = (p.R + 31) / 32 * 32;
+  p.total_tokens = d->h_cu_seqlens[d->B] ;
+  // keys to score over all ranked segments -> chunk length giving about 512 workgroups
+  int64_t keys = 0;
+  for (int b = 0; b < d->B; ++b) {
+    const int64_t n = d->h_cu_seqlens[b + 1] - d->h_cu_seqlens[b];
+    for (int h = 0; h < d->Hkv; ++h)
+      if (seg_ranked(n, d->w, d->h_budgets[h])) keys += n - d->w;
+  }
+  int64_t ch = (keys + 511) / 512;
+  ch = (ch + 127) / 128 * 128;
+  ch = std::max<int64_t>(256, std::min<int64_t>(ch, 1 << 16));
+  p.CH = (int)ch;
+  int64_t chunks = 0;
+  for (int b = 0; b < d->B; ++b) {
+    const int64_t n = d->h_cu_seqlens[b + 1] - d->h_cu_seqlens[b];
+    for (int h = 0; h < d->Hkv; ++h)
+      if (seg_ranked(n, d->w, d->h_budgets[h])) chunks += (n - d->w + ch - 1) / ch;
+  }
+  p.groups = (d->B * d->Hkv + kMaxSegPerLaunch - 1) / kMaxSegPerLaunch;
+  auto align = [](size_t x) { return (x + 255) / 256 * 256; };
+  p.part_bytes = align((size_t)std::max<int64_t>(chunks, 1) * p.Rpad * 2 * sizeof(float));
+  p.lse_bytes = align((size_t)d->B * d->Hkv * p.Rpad * sizeof(float));
+  p.score_bytes = align((size_t)std::max<int64_t>(1, (int64_t)d->Hkv * p.total_tokens) * sizeof(float));
+  p.off_part = 0;
+  p.off_lse = p.off_part + p.part_bytes;
+  p.off_imp = p.off_lse + p.lse_bytes;
+  p.off_pooled = p.off_imp + p.score_bytes;
+  p.total_bytes = p.off_pooled + p.score_bytes;
+}
+
+template <int DK, int MT, int RB>
+static void launch_bf16(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
+                        const slkv_layer_desc* d, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+  if (pass == 1)
+    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 1>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+                       (const uint16_t*)k, d->k_stride_tok, d->k_stride_head, p.R, p.Rpad, d->w, p.CH, c_log2, part, lse, imp);
+  else
+    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 2>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+                       (const uint16_t*)k, d->k_stride_tok, d->k_stride_head, p.R, p.Rpad, d->w, p.CH, c_log2, part, lse, imp);
+}
+
+template <int DK>
+static void launch_bf16_rows(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
+                             const slkv_layer_desc* d, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+  if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+  else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+  else if (p.R <= 256) launch_bf16<DK, 2, 4>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+  else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+}
+
+static void launch_score(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
+                         const slkv_layer_desc* d, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+  if (d->dtype == SLKV_BF16) {
+    if (d->d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+    else launch_bf16_rows<64>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+  } else {
+#define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
+  hipLaunchKernelGGL((score_f32_kernel<DKV, PS>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
+                     d->k_stride_tok, d->k_stride_head, p.R, p.Rpad, d->w, p.CH, c_log2, part, lse, imp)
+    if (d->d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
+    else { if (pass == 1) SLKV_F32_LAUNCH(64, 1); else SLKV_F32_LAUNCH(64, 2); }
+#undef SLKV_F32_LAUNCH
+  }
+}
+
+}  // namespace slkv
+
+using namespace slkv;
+
+extern "C" slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes) {
+  clear_error();
+  if (!bytes) return fail(SLKV_ERR_NULL, "bytes is NULL");
+  slkv_status st = validate_desc(desc);
+  if (st != SLKV_OK) return st;
+  Plan p;
+  make_plan(desc, p);
+  *bytes = p.total_bytes;
+  return SLKV_OK;
+}
+
+extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin, const void* d_k,
+                                           const void* d_v, void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                           int64_t* d_out_offsets, float* d_importance, float* d_pooled,
+                                           int64_t out_capacity_rows, void* d_workspace, size_t workspace_bytes,
+                                           void* hip_stream) {
+  clear_error();
+  slkv_status vs = validate_desc(desc);
+  if (vs != SLKV_OK) return vs;
+  if (!d_qwin || !d_k || !d_v || !d_k_out || !d_v_out || !d_kept_idx || !d_workspace)
+    return fail(SLKV_ERR_NULL, "a required device pointer is NULL");
+  const void* ptrs[] = {d_qwin, d_k, d_v, d_k_out, d_v_out, d_kept_idx, d_out_offsets, d_importance, d_pooled, d_workspace};
+  for (const void* ptr : ptrs)
+    if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(SLKV_ERR_BAD_ARG, "device pointer %p not 16-byte aligned", ptr);
+  if ((int64_t)desc->B * desc->Hq * desc->w >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "B*Hq*w >= 2^31");
+  Plan p;
+  make_plan(desc, p);
+  if (workspace_bytes < p.total_bytes)
+    return fail(SLKV_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, p.total_bytes);
+  int64_t total_kept = 0;
+  for (int b = 0; b < desc->B; ++b) {
+    const int64_t n = desc->h_cu_seqlens[b + 1] - desc->h_cu_seqlens[b];
+    for (int h = 0; h < desc->Hkv; ++h) total_kept += kept_rows(n, desc->w, desc->h_budgets[h]);
+  }
+  if (out_capacity_rows < total_kept)
+    return fail(SLKV_ERR_CAPACITY, "out_capacity_rows %lld < %lld", (long long)out_capacity_rows, (long long)total_kept);
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  unsigned char* ws = (unsigned char*)d_workspace;
+  float* part = (float*)(ws + p.off_part);
+  float* lse = (float*)(ws + p.off_lse);
+  float* imp = d_importance ? d_importance : (float*)(ws + p.off_imp);
+  float* pooled = d_pooled ? d_pooled : (float*)(ws + p.off_pooled);
+  const int G = desc->Hq / desc->Hkv;
+  const float c_log2 = (float)(1.4426950408889634 / std::sqrt((double)desc->d));
+  const int elt = desc->dtype == SLKV_BF16 ? 2 : 4;
+  const int lanes_per_row = desc->d * elt / 16;
+
+  const int S = desc->B * desc->Hkv;
+  int64_t out_run = 0;
+  for (int s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
+    SegTable tab;
+    std::memset(&tab, 0, sizeof(tab));
+    const int ns = std::min(kMaxSegPerLaunch, S - s0);
+    tab.nseg = ns;
+    int chunks = 0;
+    for (int i = 0; i < ns; ++i) {
+      const int s = s0 + i, b = s / desc->Hkv, h = s % desc->Hkv;
+      const int64_t n = desc->h_cu_seqlens[b + 1] - desc->h_cu_seqlens[b];
+      const int64_t cap = desc->h_budgets[h];
+      tab.tok_begin[i] = (int32_t)desc->h_cu_seqlens[b];
+      tab.n[i] = (int32_t)n;
+      const bool all = n <= desc->w || n <= cap;
+      tab.kkeep[i] = all ? -1 : (int32_t)std::min<int64_t>(std::max<int64_t>(cap - desc->w, 0), n - desc->w);
+      tab.out_off[i] = (int32_t)out_run;
+      out_run += kept_rows(n, desc->w, cap);
+      tab.head[i] = h;
+      tab.qrow_off[i] = (int32_t)(((int64_t)b * desc->Hq + (int64_t)h * G) * desc->w);
+      tab.score_off[i] = (int32_t)((int64_t)desc->Hkv * desc->h_cu_seqlens[b] + (int64_t)h * n);
+      tab.chunk_begin[i] = chunks;
+      tab.seg_global[i] = s;
+      if (seg_ranked(n, desc->w, cap)) chunks += (int)((n - desc->w + p.CH - 1) / p.CH);
+    }
+    tab.out_off[ns] = (int32_t)out_run;
+    tab.chunk_begin[ns] = chunks;
+    tab.total_chunks = chunks;
+    // the remaining entries repeat the end values so that searches stay inside the table
+    for (int i = ns + 1; i <= kMaxSegPerLaunch; ++i) {
+      tab.out_off[i] = tab.out_off[ns];
+      tab.chunk_begin[i] = chunks;
+    }
+    if (chunks > 0) {
+      launch_score(1, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+      hipLaunchKernelGGL(combine_kernel, dim3(ns), dim3(256), 0, st, tab, p.Rpad, part, lse);
+      launch_score(2, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+    }
+    hipLaunchKernelGGL(select_kernel, dim3(ns), dim3(kSelThreads), 0, st, tab, desc->w, desc->pool_kernel, desc->pool,
+                       imp, pooled, d_kept_idx, d_out_offsets, (int)(s0 + ns == S));
+    const int64_t rows = (int64_t)tab.out_off[ns] - tab.out_off[0];
+    if (rows > 0) {
+      const int64_t threads = rows * lanes_per_row;
+      hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, lanes_per_row,
+                         elt, (const unsigned char*)d_k, (const unsigned char*)d_v, desc->k_stride_tok,
+                         desc->k_stride_head, desc->v_stride_tok, desc->v_stride_head, (unsigned char*)d_k_out,
+                         (unsigned char*)d_v_out, d_kept_idx);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+  }
+  return SLKV_OK;
+}

@@ -1,0 +1,27 @@
+// Declarations shared by the host and device translation units of libslkv.
+#ifndef SLKV_INTERNAL_H
+#define SLKV_INTERNAL_H
+
+#include <stdint.h>
+
+#include "slkv.h"
+
+namespace slkv {
+
+constexpr int kMaxRows = 512;         // (Hq/Hkv) * w rows scored per KV head
+constexpr int kMaxPool = 63;          // widest pooling window
+constexpr int kMaxSegPerLaunch = 64;  // (sequence, KV head) segments described per kernel launch
+
+// Sets the calling thread's error detail and returns `s`.
+slkv_status fail(slkv_status s, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+// Rows kept for a segment of n tokens, window w and capacity cap (Algorithm 3).
+int64_t kept_rows(int64_t n, int64_t w, int64_t cap);
+
+// Checks everything in the descriptor that can be checked on the host.
+slkv_status validate_desc(const slkv_layer_desc* d);
+
+}  // namespace slkv
+
+#endif
