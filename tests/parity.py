@@ -1,0 +1,82 @@
+"""Shared comparison logic for the GPU parity tests (imports the oracle; test-only)."""
+
+import numpy as np
+
+import oracle
+from paper_2508_15806_amd import api
+from paper_2508_15806_amd import binding as B
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}      # relative tolerance on importance scores (task statement)
+
+
+def run_gpu(lay, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX):
+    import torch
+    call = api.LayerCall(lay.dtype, lay.B, lay.Hq, lay.Hkv, lay.d, lay.w, lay.cu_seqlens, budgets,
+                         pool_kernel, pool, debug_scores=True)
+    q = api.to_device(lay.qwin, lay.dtype)
+    k = api.to_device(lay.k, lay.dtype)
+    v = api.to_device(lay.v, lay.dtype)
+    call.run(q, k, v)
+    torch.cuda.synchronize()
+    return dict(call=call, offsets=call.out_offsets.cpu().numpy(), kept=call.kept_idx.cpu().numpy(),
+                k_out=api.to_host(call.k_out), v_out=api.to_host(call.v_out),
+                importance=call.importance.cpu().numpy(), pooled=call.pooled.cpu().numpy())
+
+
+def compare_layer(lay, budgets, gpu, pool_kernel=7, pool=B.SLKV_POOL_MAX, ref=None):
+    """Element-by-element comparison of one layer's GPU result with the oracle.
+
+    Returns a report dict: segments, exact (kept set identical), tolerant (differs only at
+    positions whose score is within tolerance of the k-th score), max_rel (importance), diffs."""
+    eps = TOL[lay.dtype]
+    if ref is None:
+        ref = oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, budgets, lay.w, pool_kernel, pool)
+    host_offs, total = B.slkv_compacted_sizes(gpu["call"].layer)
+    assert np.array_equal(ref["out_offsets"], host_offs), "host offsets differ from the oracle"
+    assert np.array_equal(ref["out_offsets"], gpu["offsets"]), "device offsets differ from the oracle"
+    G = lay.Hq // lay.Hkv
+    rep = dict(segments=0, ranked=0, exact=0, tolerant=0, max_rel=0.0, diffs=[])
+    for b in range(lay.B):
+        t0, t1 = int(lay.cu_seqlens[b]), int(lay.cu_seqlens[b + 1])
+        n = t1 - t0
+        for h in range(lay.Hkv):
+            s = b * lay.Hkv + h
+            seg = ref["segments"][s]
+            o0, o1 = int(ref["out_offsets"][s]), int(ref["out_offsets"][s + 1])
+            got = gpu["kept"][o0:o1].astype(np.int64)
+            rep["segments"] += 1
+            # whatever was selected, the gathered rows must be bit copies of those input rows
+            assert got.min(initial=0) >= 0 and got.max(initial=0) < max(n, 1)
+            assert np.array_equal(gpu["k_out"][o0:o1], lay.k[h, t0 + got]), "K gather mismatch seg %d" % s
+            assert np.array_equal(gpu["v_out"][o0:o1], lay.v[h, t0 + got]), "V gather mismatch seg %d" % s
+            want = seg["kept_idx"]
+            if seg["pooled"] is None or seg["k"] == 0:
+                assert np.array_equal(got, want), "unranked segment %d differs" % s
+                rep["exact"] += 1
+                continue
+            rep["ranked"] += 1
+            m, kk = n - lay.w, seg["k"]
+            so = lay.Hkv * t0 + h * n
+            for name, refv in (("importance", seg["importance"]), ("pooled", seg["pooled"])):
+                g = gpu[name][so:so + m].astype(np.float64)
+                floor = lay.w * G / m * 1e-3
+                rel = np.abs(g - refv) / np.maximum(np.abs(refv), floor)
+                rep["max_rel"] = max(rep["max_rel"], float(rel.max()))
+                assert rel.max() <= eps, "%s of segment %d off by %.3g (tolerance %.3g)" % (name, s, rel.max(), eps)
+            assert np.array_equal(got[kk:], want[kk:]), "window of segment %d differs" % s
+            assert (np.diff(got[:kk]) > 0).all(), "history of segment %d not ascending" % s
+            if np.array_equal(got, want):
+                rep["exact"] += 1
+                continue
+            # tolerance protocol: same size, holds every sure-in position, no sure-out position
+            tau = seg["tau"]
+            pooled = seg["pooled"]
+            sure_in = set(np.nonzero(pooled > tau * (1 + eps))[0].tolist())
+            sure_out = set(np.nonzero(pooled < tau * (1 - eps))[0].tolist())
+            gset = set(got[:kk].tolist())
+            assert len(gset) == kk
+            assert sure_in <= gset, "segment %d misses a clearly-in position" % s
+            assert not (gset & sure_out), "segment %d holds a clearly-out position" % s
+            rep["tolerant"] += 1
+            rep["diffs"].append((s, sorted(gset ^ set(want[:kk].tolist()))))
+    return rep

@@ -1,0 +1,146 @@
+"""GPU parity of slkv_compress_layer against the float64 oracle, through the C ABI.
+
+Bar: out offsets and kept-index sets bit-exact (positions whose pooled score is within the
+tolerance of the k-th score may differ and are reported); gathered K/V bit-exact; importance
+and pooled scores within 2e-3 (bf16 inputs) / 1e-5 (fp32 inputs) relative."""
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2508_15806_amd import binding as B
+from paper_2508_15806_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def parity():
+    import parity as p
+    return p
+
+
+def budgets_for(lay, inf=None, avg=None, fixed=None):
+    inf = lay.meta["inf"] if inf is None else inf
+    avg = lay.meta["avg"] if avg is None else avg
+    fixed = lay.meta["fixed"] if fixed is None else fixed
+    got = B.slkv_allocate_budgets(inf, lay.Hkv, avg, fixed)
+    assert got.tolist() == oracle.allocate_budgets(np.asarray(inf).tolist(), lay.Hq, lay.Hkv, avg, fixed)
+    return got
+
+
+def check(lay, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX, require_exact=False):
+    p = parity()
+    gpu = p.run_gpu(lay, budgets, pool_kernel, pool)
+    rep = p.compare_layer(lay, budgets, gpu, pool_kernel, pool)
+    print("segments %d ranked %d exact %d tolerant %d max_rel %.3g diffs %s" % (
+        rep["segments"], rep["ranked"], rep["exact"], rep["tolerant"], rep["max_rel"], rep["diffs"][:4]), flush=True)
+    if require_exact:
+        assert rep["tolerant"] == 0
+    return rep
+
+
+def test_config1_fp32():
+    lay = wl.config1()
+    rep = check(lay, budgets_for(lay)[0])
+    assert rep["ranked"] == 4
+
+
+def test_config2_bf16():
+    lay = wl.config2()
+    bud = budgets_for(lay)[0]
+    assert int(bud.sum()) == 128 * 8
+    rep = check(lay, bud)
+    assert rep["ranked"] == 8
+
+
+@pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 16, 128), (4, 2, 16, 128), (8, 2, 16, 128), (8, 2, 32, 128),
+                                        (16, 2, 32, 128), (4, 4, 24, 64), (8, 2, 20, 64), (32, 8, 16, 64)])
+def test_bf16_row_shapes_and_ragged_tails(Hq, Hkv, w, d):
+    # lengths chosen so that the history is not a multiple of the 32-key MFMA tile
+    lay = wl.make_layer((101, Hq, w, d), [1000 + w + 7, 333 + w], Hq, Hkv, d, w, dtype="bf16", bias_frac=0.03)
+    bud = np.array([w + 40 + 13 * h for h in range(Hkv)], dtype=np.int32)
+    check(lay, bud)
+
+
+@pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 8, 64), (4, 2, 32, 128), (8, 1, 40, 64)])
+def test_fp32_shapes(Hq, Hkv, w, d):
+    lay = wl.make_layer((102, Hq, w, d), [700 + w + 5, 90], Hq, Hkv, d, w, dtype="f32", bias_frac=0.03)
+    bud = np.array([w + 30 + 11 * h for h in range(Hkv)], dtype=np.int32)
+    check(lay, bud)
+
+
+def test_edge_segments():
+    # empty sequence, n <= w, n <= capacity, capacity <= window, capacity == n - 1
+    w = 16
+    lay = wl.make_layer((103,), [0, 10, 16, 200, 17, 300], 4, 2, 128, w, dtype="bf16", bias_frac=0.05)
+    for bud in ([200, 5], [299, 16], [17, 0], [1000, 1000]):
+        check(lay, np.array(bud, dtype=np.int32))
+
+
+@pytest.mark.parametrize("pool,kernel", [(B.SLKV_POOL_MAX, 1), (B.SLKV_POOL_MAX, 3), (B.SLKV_POOL_MAX, 13),
+                                         (B.SLKV_POOL_AVG, 7), (B.SLKV_POOL_NONE, 7)])
+def test_pool_modes(pool, kernel):
+    lay = wl.make_layer((104, kernel), [900], 8, 2, 128, 16, dtype="bf16", bias_frac=0.05)
+    check(lay, np.array([100, 333], dtype=np.int32), kernel, pool)
+
+
+def test_heavy_ties_are_cut_by_lowest_position():
+    # identical keys everywhere: every importance score ties, so the kept set must be the lowest positions
+    lay = wl.make_layer((105,), [600], 4, 2, 128, 16, dtype="bf16")
+    lay.k[:, :, :] = lay.k[:, :1, :]
+    rep = check(lay, np.array([100, 50], dtype=np.int32), require_exact=True)
+    assert rep["ranked"] == 2
+    # two alternating key values: long plateaus after max pooling
+    lay = wl.make_layer((106,), [1500], 4, 2, 128, 16, dtype="bf16")
+    lay.k[:, 1::2, :] = lay.k[:, 1:2, :]
+    lay.k[:, 0::2, :] = lay.k[:, 0:1, :]
+    check(lay, np.array([200, 700], dtype=np.int32), require_exact=True)
+
+
+def test_many_segments_span_several_launch_groups():
+    lens = [150 + 7 * i for i in range(40)]                        # 40 sequences x 2 heads = 80 segments
+    lay = wl.make_layer((107,), lens, 4, 2, 64, 8, dtype="bf16", bias_frac=0.05)
+    check(lay, np.array([40, 100], dtype=np.int32))
+
+
+def test_two_runs_are_bit_identical():
+    p = parity()
+    lay = wl.config2()
+    bud = budgets_for(lay)[0]
+    a = p.run_gpu(lay, bud)
+    b = p.run_gpu(lay, bud)
+    for key in ("offsets", "kept", "k_out", "v_out", "importance", "pooled"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_long_segment_multi_round_compaction():
+    # history longer than one compaction round (128 * 1024 positions) and than 2^16 kept rows
+    lay = wl.make_layer((108,), [140000], 2, 1, 64, 8, dtype="bf16", bias_frac=0.01)
+    check(lay, np.array([70008], dtype=np.int32))
+
+
+@pytest.mark.parametrize("layer", [0, 1, 5])
+def test_config3_layers_all_budgets(layer):
+    p = parity()
+    lay = wl.config3_layer(layer)
+    inf = wl.config3_inf()
+    ref = None
+    for avg in wl.C3_BUDGETS:
+        bud = budgets_for(lay, inf, avg, 16)[layer]
+        gpu = p.run_gpu(lay, bud)
+        rep = p.compare_layer(lay, bud, gpu)
+        print("c3 layer %d avg %d: ranked %d exact %d tolerant %d max_rel %.3g" % (
+            layer, avg, rep["ranked"], rep["exact"], rep["tolerant"], rep["max_rel"]), flush=True)
+
+
+def test_config5_ragged_long_context():
+    p = parity()
+    lay = wl.config5()
+    inf = wl.config3_inf()
+    row = wl.config5_layer_row(inf)
+    bud = budgets_for(lay, inf, 512, 64)[row]
+    gpu = p.run_gpu(lay, bud)
+    rep = p.compare_layer(lay, bud, gpu)
+    print("c5: segments %d ranked %d exact %d tolerant %d max_rel %.3g" % (
+        rep["segments"], rep["ranked"], rep["exact"], rep["tolerant"], rep["max_rel"]), flush=True)
+    assert rep["segments"] == 32
