@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the SurfaceLogicKV prefill KV-compression pass on one MI355X.
+
+A step is one slkv_compress_layer call (scoring, softmax importance, pooling, top-k, gather;
+budgets precomputed with slkv_allocate_budgets) over one layer of the 32-layer
+Llama-3-8B-shaped prefill: bf16, 32 query / 8 KV heads, head_dim 128, prefix 32768, window 64,
+average budget 256 per KV head (fixed 16), INF_sc map with 2% spikes.  The timed loop cycles
+through distinct layers (4 GiB of K/V, far above the 256 MB Infinity Cache), inputs resident
+in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers 32] [--no-stage1]
+"""
+
+import argparse
+import concurrent.futures as cf
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/); None until measured for the current kernels.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=32, help="distinct layers resident in HBM")
+    ap.add_argument("--avg", type=int, default=256, help="average budget per KV head (64, 256 or 1024)")
+    ap.add_argument("--no-stage1", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2508_15806_amd import api, binding as B, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    B.lib()                                            # fail loudly when the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    NL = args.layers
+    Hq, Hkv, d, w, n = 32, 8, 128, 64, 32768
+    G = Hq // Hkv
+    inf = wl.config3_inf()
+    budgets = B.slkv_allocate_budgets(inf, Hkv, args.avg, 16)
+
+    t0 = time.time()
+    workers = max(1, min(16, len(os.sched_getaffinity(0))))
+    with cf.ThreadPoolExecutor(workers) as ex:
+        layers = list(ex.map(lambda l: wl.config3_layer(l, n), range(NL)))
+    gen_s = time.time() - t0
+
+    calls, dq, dk, dv = [], [], [], []
+    for l, lay in enumerate(layers):
+        calls.append(api.LayerCall("bf16", 1, Hq, Hkv, d, w, lay.cu_seqlens, budgets[l % budgets.shape[0]]))
+        dq.append(api.to_device(lay.qwin, "bf16"))
+        dk.append(api.to_device(lay.k, "bf16"))
+        dv.append(api.to_device(lay.v, "bf16"))
+    torch.cuda.synchronize()
+
+    def step(i):
+        l = i % NL
+        calls[l].run(dq[l], dk[l], dv[l])
+
+    # per-step algorithmic work
+    def layer_work(l):
+        bud = budgets[l % budgets.shape[0]]
+        ranked = [h for h in range(Hkv) if n > bud[h] > w]
+        m = n - w
+        kept = int(calls[l].total_kept)
+        flops = 2.0 * G * w * d * m * len(ranked)                  # one scoring pass (Eq. 7)
+        byts = (len(ranked) * m * d * 2                            # K once
+                + Hq * w * d * 2                                   # window queries
+                + len(ranked) * m * 4 * 2                          # importance written + read
+                + kept * 4                                         # kept indices
+                + kept * d * 2 * 2 * 2)                            # K and V rows read + written
+        return flops, byts, kept, len(ranked)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_total = ev0.elapsed_time(ev1)
+    ms_step = ms_total / args.steps
+    tokens_per_s = n / (ms_step * 1e-3)
+
+    work = [layer_work((args.warmup + i) % NL) for i in range(args.steps)]
+    flops_step = float(np.mean([x[0] for x in work]))
+    bytes_step = float(np.mean([x[1] for x in work]))
+
+    # same loop again with an event pair around every kernel launch
+    nrec = args.steps * 8
+    B.slkv_profile_begin(nrec)
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    recs = B.slkv_profile_end(nrec)
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    kernel_ms = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+    kernel_launches = {k: len(v) / args.steps for k, v in per_kernel.items()}
+    dom = max(("score_stats", "score_accum"), key=lambda k: kernel_ms.get(k, 0.0))
+    # launches of the scoring kernels only happen on layers with ranked heads
+    ranked_flops = [x[0] for x in work if x[3] > 0]
+    flops_launch = float(np.mean(ranked_flops)) if ranked_flops else 0.0
+    dom_ms = kernel_ms.get(dom, float("nan"))
+    achieved_tflops = flops_launch / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved_tflops, 2),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5),
+                "flops_per_launch": flops_launch}
+
+    out = {
+        "metric": "prefix KV tokens compressed/sec per layer (1 GPU)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3: 32-layer Llama-3-8B-shaped prefill compression, one layer per step, "
+                               "32q/8kv heads, head_dim 128, prefix 32768, window 64, pool max-7, "
+                               "avg budget %d (fixed 16)" % args.avg,
+                   "distinct_layers": NL, "avg_budget": args.avg, "input_gen_s": round(gen_s, 1)},
+        "roofline": roofline,
+        "layer": {"algorithmic_bytes": bytes_step, "hbm_GBs": round(bytes_step / (ms_step * 1e-3) / 1e9, 1),
+                  "hbm_frac": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "one_pass_TFLOPs": round(flops_step / (ms_step * 1e-3) / 1e12, 2),
+                  "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
+                  "kernel_launches_per_step": kernel_launches,
+                  "kernel_sum_ms": round(sum(kernel_ms[k] * kernel_launches[k] for k in kernel_ms), 5)},
+    }
+
+    # other budgets of the sweep (same inputs, shorter loops)
+    sweep = {}
+    for avg in wl.C3_BUDGETS:
+        if avg == args.avg:
+            continue
+        bud = B.slkv_allocate_budgets(inf, Hkv, avg, 16)
+        cs = [api.LayerCall("bf16", 1, Hq, Hkv, d, w, layers[l].cu_seqlens, bud[l % 32]) for l in range(NL)]
+        for i in range(NL):
+            cs[i % NL].run(dq[i % NL], dk[i % NL], dv[i % NL])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(NL, args.steps // 2)
+        e0.record()
+        for i in range(reps):
+            cs[i % NL].run(dq[i % NL], dk[i % NL], dv[i % NL])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        sweep["avg%d" % avg] = {"ms_per_step": round(ms, 5), "tokens_per_s": round(n / (ms * 1e-3), 1)}
+        del cs
+    out["budget_sweep"] = sweep
+
+    # Stage 1 (Algorithm 1) on the 32 x 32 heads x 16 steps x 16384 attention rows (1 GiB)
+    if not args.no_stage1:
+        nr = wl.config4()
+        rows = torch.from_numpy(nr.rows).to(dev)
+        acc, sc = api.score_heads(rows, nr.needle_start, nr.needle_len, nr.topk)
+        torch.cuda.synchronize()
+        reps = 5
+        B.slkv_profile_begin(reps * 2)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            api.score_heads(rows, nr.needle_start, nr.needle_len, nr.topk, acc)
+        e1.record()
+        torch.cuda.synchronize()
+        recs1 = B.slkv_profile_end(reps * 2)
+        ms = e0.elapsed_time(e1) / reps
+        rc_ms = float(np.mean([m_ for k_, m_ in recs1 if k_ == "row_cells"]))
+        nbytes = rows.numel() * 4
+        out["stage1"] = {"workload": "c4: 32x32 heads x 16 decode rows x 16384 weights fp32",
+                         "ms_per_call": round(ms, 4), "rows_per_s": round(rows.shape[0] * rows.shape[1] * rows.shape[2] / (ms * 1e-3), 1),
+                         "row_cells_ms": round(rc_ms, 4), "hbm_GBs": round(nbytes / (rc_ms * 1e-3) / 1e9, 1),
+                         "hbm_frac": round(nbytes / (rc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del rows
+
+    # CPU baseline: the float64 oracle, as it stands, on a bounded sample of the same workload,
+    # also used as the parity check of what the GPU just produced.
+    if not args.no_cpu:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        ncpu = min(args.cpu_layers, NL)
+        t0 = time.time()
+        refs = []
+        for l in range(ncpu):
+            lay = layers[l]
+            refs.append(oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, budgets[l], w, 7))
+        cpu_s = time.time() - t0
+        out["cpu_baseline"] = {"value": round(ncpu * n / cpu_s, 1), "unit": "tokens/s", "cores": int(cores),
+                               "kind": "oracle", "sample": "%d of the %d layers of the same workload, float64 numpy" % (ncpu, NL)}
+        exact = 0
+        total = 0
+        for l in range(ncpu):
+            calls[l].run(dq[l], dk[l], dv[l])
+            torch.cuda.synchronize()
+            kept = calls[l].kept_idx.cpu().numpy()
+            offs = refs[l]["out_offsets"]
+            for s in range(Hkv):
+                total += 1
+                exact += int(np.array_equal(kept[offs[s]:offs[s + 1]], refs[l]["segments"][s]["kept_idx"]))
+        out["parity"] = {"segments_checked": total, "kept_sets_identical": exact}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,8 @@
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every
- *     buffer; the library allocates no device memory and keeps no state between calls.
+ *     buffer; the library allocates no device memory and keeps no state between calls
+ *     (the optional kernel-timing recorder at the end of this header aside).
  *   - slkv_score_heads and slkv_compress_layer only enqueue work on `hip_stream` (a
  *     hipStream_t passed as void*, NULL = the default stream) and return without
  *     synchronising.  Host-side descriptors are consumed before the call returns.
@@ -157,6 +158,29 @@ slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin,
                                 int64_t* d_out_offsets, float* d_importance, float* d_pooled,
                                 int64_t out_capacity_rows,
                                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------ kernel timing -----
+ * Optional instrumentation for benchmarks: between slkv_profile_begin and slkv_profile_end
+ * every kernel the library launches is bracketed by a HIP event pair on the call's stream.
+ * slkv_profile_begin creates the events it needs (the only state the library ever keeps);
+ * slkv_profile_end waits for the recorded events, writes up to `capacity` records in launch
+ * order and sets *count to the number recorded.  Process-wide; not meant for production.
+ */
+typedef enum {
+  SLKV_K_SCORE_STATS = 0,   /* logits + per-row running max / sum-exp */
+  SLKV_K_COMBINE = 1,       /* per-row log-sum-exp over the key chunks */
+  SLKV_K_SCORE_ACCUM = 2,   /* logits + exp(logit - lse) summed down the rows */
+  SLKV_K_SELECT = 3,        /* pooling + top-k */
+  SLKV_K_GATHER = 4,        /* K/V row gather */
+  SLKV_K_ROW_CELLS = 5,     /* Stage 1: per-row weight cells */
+  SLKV_K_HEAD_REDUCE = 6    /* Stage 1: per-head sums and scores */
+} slkv_kernel_id;
+typedef struct {
+  int32_t kernel; /* slkv_kernel_id */
+  float ms;       /* elapsed time between the launch's two events */
+} slkv_kernel_time;
+slkv_status slkv_profile_begin(int32_t max_records);
+slkv_status slkv_profile_end(slkv_kernel_time* h_records, int32_t capacity, int32_t* count);
 
 #ifdef __cplusplus
 }

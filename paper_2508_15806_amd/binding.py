@@ -23,13 +23,20 @@ STATUS_NAMES = {0: "SLKV_OK", 1: "SLKV_ERR_NULL", 2: "SLKV_ERR_BAD_ARG", 3: "SLK
 
 EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads",
            "slkv_score_heads_workspace_bytes", "slkv_allocate_budgets", "slkv_fixed_from_beta",
-           "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer"]
+           "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer",
+           "slkv_profile_begin", "slkv_profile_end"]
+
+KERNEL_NAMES = ["score_stats", "combine", "score_accum", "select", "gather", "row_cells", "head_reduce"]
 
 
 class SlkvError(RuntimeError):
     def __init__(self, status, detail):
         self.status = status
         super().__init__("%s: %s" % (STATUS_NAMES.get(status, status), detail))
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("ms", C.c_float)]
 
 
 class LayerDesc(C.Structure):
@@ -74,6 +81,10 @@ def lib():
         L.slkv_score_heads.restype = C.c_int
         L.slkv_score_heads.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.slkv_profile_begin.restype = C.c_int
+        L.slkv_profile_begin.argtypes = [C.c_int32]
+        L.slkv_profile_end.restype = C.c_int
+        L.slkv_profile_end.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -158,3 +169,15 @@ def slkv_score_heads(rows, needle_start, needle_len, topk, acc, scores, workspac
     _check(lib().slkv_score_heads(_ptr(rows), L, H, T, n, int(needle_start), int(needle_len), int(topk), _ptr(acc),
                                   _ptr(scores), _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                   _stream(stream)))
+
+
+def slkv_profile_begin(max_records):
+    _check(lib().slkv_profile_begin(int(max_records)))
+
+
+def slkv_profile_end(capacity):
+    """Returns a list of (kernel name, milliseconds) in launch order."""
+    recs = (KernelTime * capacity)()
+    cnt = C.c_int32(0)
+    _check(lib().slkv_profile_end(C.cast(recs, C.c_void_p), capacity, C.byref(cnt)))
+    return [(KERNEL_NAMES[recs[i].kernel], float(recs[i].ms)) for i in range(min(cnt.value, capacity))]

@@ -13,7 +13,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslkv.so")
 
 HIP_SOURCES = ["compress.hip", "stage1.hip"]
-HOST_SOURCES = ["slkv_host.cpp"]
+HOST_SOURCES = ["slkv_host.cpp", "timing.cpp"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # packed fp32 VALU ops are kept off for device code
@@ -37,7 +37,7 @@ def build(verbose=True):
     for src in HOST_SOURCES:
         obj = os.path.join(objdir, src + ".o")
         # host arithmetic (budget allocation) must not be contracted into FMAs
-        run([hipcc] + COMMON + ["-ffp-contract=off", "-x", "c++", "-c", os.path.join(CSRC, src), "-o", obj])
+        run([hipcc] + COMMON + ["-ffp-contract=off", "-x", "hip", "--offload-arch=gfx950", "-c", os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
     run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
     return LIB

@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #include "device_utils.h"
@@ -36,8 +37,10 @@ struct SegTable {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (register friendly)
+
 union Pack16 {
-  uint4 u;
+  u32x4 u;
   bf16x8 b;
 };
 
@@ -63,24 +66,33 @@ __device__ __forceinline__ void merge_stats(float& m, float& s, float m2, float 
 
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA scoring.  One workgroup (4 waves) owns one chunk of history keys of one segment.
-// Wave (rb, ks): rows [rb*32*MT, (rb+1)*32*MT) of the G*w query rows, key sub-tile ks of each
-// LDS tile.  The 32x32x16 MFMA takes, per lane, 8 consecutive k-elements of row (lane%32) at
-// k offset 8*(lane/32) for both operands, and returns for result register i the element at
-// row 8*(i/4) + 4*(lane/32) + i%4, column lane%32.
+// K is staged in LDS in tiles of 64 keys (two buffers); up to kPrefetch further tiles are in
+// flight from HBM into registers.  Wave (rb, ks) holds rows [rb*32*MT, (rb+1)*32*MT) of the
+// G*w query rows in registers for the whole chunk and works on the 32-key sub-tiles
+// ks, ks+KS, .. of every tile.  The 32x32x16 MFMA takes, per lane, 8 consecutive k-elements of
+// row (lane%32) at k offset 8*(lane/32) for both operands, and returns in result register i the
+// element at row 8*(i/4) + 4*(lane/32) + i%4, column lane%32.
 //   PASS 1: D[key][qrow]: a lane owns one query row per MFMA tile -> running (max, sum-exp).
 //   PASS 2: D[qrow][key]: a lane owns one key column -> sum over rows of exp2(x - lse[row]).
+// Rows beyond R and keys beyond the chunk are loaded from a clamped (valid) address and masked.
+constexpr int kTileKeys = 64;
+constexpr int kPrefetch = 2;
+
 template <int DK, int MT, int RB, int PASS>
-__global__ __launch_bounds__(256) void score_bf16_kernel(const SegTable tab, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(const SegTable tab, const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ kmat, int64_t k_stride_tok,
                                                          int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                          float c_log2, float* __restrict__ part,
                                                          const float* __restrict__ lse, float* __restrict__ imp) {
-  constexpr int KS = 4 / RB;
-  constexpr int TK = 32 * KS;
+  constexpr int KS = 4 / RB;               // waves along the keys
+  constexpr int TK = kTileKeys;
+  constexpr int NSUB = TK / 32 / KS;       // 32-key sub-tiles per wave per tile
   constexpr int KK = DK / 16;
-  constexpr int ROWB = DK * 2 + 16;
-  constexpr int CPR = DK * 2 / 16;
-  constexpr int LPT = (TK * CPR + 255) / 256;
+  constexpr int ROWB = DK * 2 + 16;        // padded LDS row: conflict-free 16-byte reads down a column
+  constexpr int CPR = DK * 2 / 16;         // 16-byte pieces per key row
+  constexpr int LPT = TK * CPR / 256;      // pieces per thread per tile
+  constexpr int NPF = kPrefetch;
+  static_assert(TK * CPR % 256 == 0, "tile must divide over the workgroup");
   __shared__ __attribute__((aligned(16))) unsigned char ktile[2][TK * ROWB];
   __shared__ float red[2][RB][TK];
   __shared__ float2 comb[KS][RB * 32 * MT];
@@ -95,23 +107,47 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const SegTable tab, con
   const int m = tab.n[seg] - w;
   const int key_begin = chunk * CH;
   const int key_end = min(m, key_begin + CH);
-  const int ntiles = (key_end - key_begin + TK - 1) / TK;
-  const uint16_t* kbase = kmat + (int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok;
+  // tiles are processed in pairs (one per register slot); a surplus tile is fully masked
+  const int ntiles = ((key_end - key_begin + TK - 1) / TK + 1) & ~1;
+  // uniform 64-bit base of the segment's keys + 32-bit byte offsets (the host checks the range)
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(
+      kmat + (int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok);
+  const uint32_t row_bytes = (uint32_t)k_stride_tok * 2u;
+  const uint32_t piece_off = (uint32_t)(tid % CPR) * 16u;
+  const int piece_row = tid / CPR;
+
+  u32x4 pf0[LPT], pf1[LPT];
+  auto issue_tile = [&](int t, u32x4 (&pf)[LPT]) __attribute__((always_inline)) {
+    const int key0 = key_begin + t * TK + piece_row;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int key = min(key0 + i * (256 / CPR), key_end - 1);
+      pf[i] = *reinterpret_cast<const u32x4*>(kbase + ((uint32_t)key * row_bytes + piece_off));
+    }
+  };
+  auto store_tile = [&](const u32x4 (&pf)[LPT], int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int idx = i * 256 + tid;
+      *reinterpret_cast<u32x4*>(&ktile[buf][(idx / CPR) * ROWB + (idx % CPR) * 16]) = pf[i];
+    }
+  };
+  static_assert(NPF == 2, "the tile loop below is written out for two register slots");
+  issue_tile(0, pf0);
+  issue_tile(1, pf1);
 
   // query rows of this wave, kept in registers for the whole chunk
   bf16x8 qreg[MT][KK];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int row = rb * 32 * MT + mt * 32 + l32;
+    const int row = min(rb * 32 * MT + mt * 32 + l32, R - 1);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       Pack16 p;
-      p.u = make_uint4(0, 0, 0, 0);
-      if (row < R) p.u = *reinterpret_cast<const uint4*>(q + ((int64_t)tab.qrow_off[seg] + row) * DK + kk * 16 + half * 8);
+      p.u = *reinterpret_cast<const u32x4*>(q + ((int64_t)tab.qrow_off[seg] + row) * DK + kk * 16 + half * 8);
       qreg[mt][kk] = p.b;
     }
   }
-
   float lse_r[PASS == 2 ? MT : 1][16];
   if (PASS == 2) {
 #pragma unroll
@@ -129,97 +165,96 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const SegTable tab, con
     s_run[mt] = 0.f;
   }
 
-  uint4 pf[LPT];
-  auto load_tile = [&](int t) {
-    const int key0 = key_begin + t * TK;
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int idx = i * 256 + tid;
-      const int row = idx / CPR, c = idx % CPR;
-      pf[i] = make_uint4(0, 0, 0, 0);
-      if (idx < TK * CPR && key0 + row < key_end)
-        pf[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)(key0 + row) * k_stride_tok + c * 8);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int idx = i * 256 + tid;
-      const int row = idx / CPR, c = idx % CPR;
-      if (idx < TK * CPR) *reinterpret_cast<uint4*>(&ktile[buf][row * ROWB + c * 16]) = pf[i];
-    }
-  };
-
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-
-  for (int t = 0; t < ntiles; ++t) {
+  // one tile: registers -> LDS, refill the register slot, barrier, MFMAs + epilogue
+  auto do_tile = [&](int t, u32x4 (&pf)[LPT], auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;   // the tile may reach past key_end
     const int buf = t & 1;
-    if (t + 1 < ntiles) load_tile(t + 1);
-
-    bf16x8 kreg[KK];
+    store_tile(pf, buf);
+    issue_tile(t + NPF, pf);   // past the chunk end every piece comes from one clamped row
+    __syncthreads();
+    if (PASS == 2 && t > 0 && tid < TK) {          // column sums of the previous tile
+      float v = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      Pack16 p;
-      p.u = *reinterpret_cast<const uint4*>(&ktile[buf][(ks * 32 + l32) * ROWB + kk * 32 + half * 16]);
-      kreg[kk] = p.b;
+      for (int r = 0; r < RB; ++r) v += red[buf ^ 1][r][tid];
+      const int key = key_begin + (t - 1) * TK + tid;
+      if (key < key_end) imp[tab.score_off[seg] + key] = v;
     }
-    const int key0 = key_begin + t * TK + ks * 32;   // first key of this wave's sub-tile
-    float colsum = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      f32x16 acc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int sb = 0; sb < NSUB; ++sb) {
+      __builtin_amdgcn_sched_barrier(0);   // keep one sub-tile's operands live at a time
+      const int sub = ks + sb * KS;
+      const int key0 = key_begin + t * TK + sub * 32;   // first key of this sub-tile
+      bf16x8 kreg[KK];
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        if (PASS == 1)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk], qreg[mt][kk], acc, 0, 0, 0);
-        else
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[mt][kk], kreg[kk], acc, 0, 0, 0);
+        Pack16 p;
+        p.u = *reinterpret_cast<const u32x4*>(&ktile[buf][(sub * 32 + l32) * ROWB + kk * 32 + half * 16]);
+        kreg[kk] = p.b;
       }
-      if (PASS == 1) {
-        // lane: query row mt*32 + l32, keys key0 + 8*(i/4) + 4*half + i%4
-        if (key0 + 32 > key_end) {
+      float colsum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (key0 + 8 * (i >> 2) + 4 * half + (i & 3) >= key_end) acc[i] = -INFINITY;
+      for (int mt = 0; mt < MT; ++mt) {
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          if (PASS == 1)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk], qreg[mt][kk], acc, 0, 0, 0);
+          else
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[mt][kk], kreg[kk], acc, 0, 0, 0);
         }
-        float mx = acc[0];
+        if (PASS == 1) {
+          // lane: query row mt*32 + l32, keys key0 + 8*(i/4) + 4*half + i%4
+          if (MASKED && key0 + 32 > key_end) {
 #pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, acc[i]);
-        const float mn = fmaxf(m_run[mt], mx * c_log2);
-        const float mu = mn == -INFINITY ? 0.f : mn;
-        float sum = 0.f;
+            for (int i = 0; i < 16; ++i)
+              if (key0 + 8 * (i >> 2) + 4 * half + (i & 3) >= key_end) acc[i] = -INFINITY;
+          }
+          float mx = fmaxf(acc[0], acc[1]);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c_log2, -mu));
-        s_run[mt] = s_run[mt] * fast_exp2(m_run[mt] - mu) + sum;
-        m_run[mt] = mn;
-      } else {
-        // lane: key key0 + l32, query rows mt*32 + 8*(i/4) + 4*half + i%4
+          for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(acc[i], acc[i + 1]));
+          const float mn = fmaxf(m_run[mt], mx * c_log2);
+          const float mu = mn == -INFINITY ? 0.f : mn;
+          float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], c_log2, -lse_r[mt][i]));
+          for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c_log2, -mu));
+          s_run[mt] = s_run[mt] * fast_exp2(m_run[mt] - mu) + sum;
+          m_run[mt] = mn;
+        } else {
+          // lane: key key0 + l32, query rows mt*32 + 8*(i/4) + 4*half + i%4
+#pragma unroll
+          for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[i], c_log2, -lse_r[mt][i]));
+        }
+      }
+      if (PASS == 2) {
+        colsum += __shfl_xor(colsum, 32, 64);
+        if (half == 0) red[buf][rb][sub * 32 + l32] = colsum;
       }
     }
-    if (PASS == 2) {
-      colsum += __shfl_xor(colsum, 32, 64);
-      if (half == 0) red[buf][rb][ks * 32 + l32] = colsum;
-    }
-    if (t + 1 < ntiles) store_tile(buf ^ 1);
-    __syncthreads();
-    if (PASS == 2) {
-      if (tid < TK) {
-        float v = 0.f;
-#pragma unroll
-        for (int r = 0; r < RB; ++r) v += red[buf][r][tid];
-        const int key = key_begin + t * TK + tid;
-        if (key < key_end) imp[tab.score_off[seg] + key] = v;
-      }
-    }
-  }
+  };
 
-  if (PASS == 1) {
+  // everything loaded so far (first two tiles, Q, lse) has to be complete here; inside the loop
+  // only the two tile slots stay in flight, so the waits there can be partial
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  for (int t0 = 0; t0 < ntiles - NPF; t0 += NPF) {
+    do_tile(t0, pf0, std::false_type{});
+    do_tile(t0 + 1, pf1, std::false_type{});
+  }
+  do_tile(ntiles - 2, pf0, std::true_type{});   // only the last pair can reach past the chunk end
+  do_tile(ntiles - 1, pf1, std::true_type{});
+
+  if (PASS == 2) {
+    __syncthreads();
+    if (tid < TK) {
+      const int t = ntiles - 1;
+      float v = 0.f;
+#pragma unroll
+      for (int r = 0; r < RB; ++r) v += red[t & 1][r][tid];
+      const int key = key_begin + t * TK + tid;
+      if (key < key_end) imp[tab.score_off[seg] + key] = v;
+    }
+  } else {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       float m2 = __shfl_xor(m_run[mt], 32, 64);
@@ -317,50 +352,61 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const SegTable tab, cons
   }
 }
 
-// Per-row log-sum-exp (log2 domain) over a segment's chunks, chunks taken in order.
+// Per-row log-sum-exp (log2 domain) over a segment's chunks.  Block = 16 rows x 16 lanes; lane c
+// folds chunks c, c+16, ... in order, then the 16 partial results are merged by a butterfly.
 __global__ __launch_bounds__(256) void combine_kernel(const SegTable tab, int Rpad, const float* __restrict__ part,
                                                       float* __restrict__ lse) {
-  const int seg = blockIdx.x;
+  const int seg = blockIdx.y;
   const int c0 = tab.chunk_begin[seg], c1 = tab.chunk_begin[seg + 1];
   if (c0 == c1) return;
-  for (int row = threadIdx.x; row < Rpad; row += 256) {
-    float mm = -INFINITY, ss = 0.f;
-    for (int c = c0; c < c1; ++c)
-      merge_stats(mm, ss, part[((int64_t)c * Rpad + row) * 2], part[((int64_t)c * Rpad + row) * 2 + 1]);
-    lse[seg * Rpad + row] = ss > 0.f ? mm + log2f(ss) : INFINITY;
+  const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int cl = threadIdx.x & 15;
+  float mm = -INFINITY, ss = 0.f;
+  if (row < Rpad) {
+    for (int c = c0 + cl; c < c1; c += 16) {
+      const float2 ps = *reinterpret_cast<const float2*>(part + ((int64_t)c * Rpad + row) * 2);
+      merge_stats(mm, ss, ps.x, ps.y);
+    }
   }
+#pragma unroll
+  for (int dlt = 8; dlt > 0; dlt >>= 1) {
+    const float m2 = __shfl_xor(mm, dlt, 64), s2 = __shfl_xor(ss, dlt, 64);
+    merge_stats(mm, ss, m2, s2);
+  }
+  if (row < Rpad && cl == 0) lse[seg * Rpad + row] = ss > 0.f ? mm + log2f(ss) : INFINITY;
 }
 
 // ------------------------------------------------------------------------------------------
 // Pooling + top-k of one segment per workgroup (Algorithm 3, steps 7-8).  Writes the kept
 // positions: history positions ascending, then the window.
+//
+// The history is processed in rounds of 32768 positions; thread t owns 32 consecutive
+// positions of a round (values reach it through an LDS transposition of coalesced loads), so
+// pooling is a sliding window in registers, equal neighbours share one histogram update and
+// the ordered compaction needs one block scan per round.  A history of one round stays in
+// registers from the first load to the last store.
+// The k-th largest pooled score is found by a radix select whose digits are taken relative to
+// the segment's own [min, max] of score bit patterns (scores are >= 0, so the bit pattern is
+// monotone): 11 bits per level over the remaining range, at most three levels.
 constexpr int kSelThreads = 1024;
+constexpr int kSelEPT = 32;
+constexpr int kSelRound = kSelThreads * kSelEPT;
+constexpr int kSelHaloMax = kMaxPool / 2;
+constexpr int kSelStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * kSelHaloMax) >> 5) + 8;
 
-__device__ __forceinline__ float pooled_at(const float* __restrict__ I, int j, int m, int radius, int mode, float inv_p) {
-  if (mode == SLKV_POOL_NONE || radius == 0) return I[j];
-  const int lo = max(0, j - radius), hi = min(m - 1, j + radius);
-  if (mode == SLKV_POOL_MAX) {
-    float v = I[lo];
-    for (int t = lo + 1; t <= hi; ++t) v = fmaxf(v, I[t]);
-    return v;
-  }
-  float v = 0.f;
-  for (int t = lo; t <= hi; ++t) v += I[t];
-  return v * inv_p;
-}
+__device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
 
+template <int RADIUS>   // pooling radius known at compile time (0..3), or -1: any radius, window read from LDS
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab, int w, int pool_kernel, int pool_mode,
-                                                             const float* __restrict__ imp, float* __restrict__ pooled,
-                                                             int32_t* __restrict__ kept_idx,
+                                                             int write_pooled, const float* __restrict__ imp,
+                                                             float* __restrict__ pooled, int32_t* __restrict__ kept_idx,
                                                              int64_t* __restrict__ d_out_offsets, int is_last_group) {
-  constexpr int NT = kSelThreads;
-  constexpr int NW = NT / 64;
-  constexpr int SUPER = 128;                       // tiles of NT elements per compaction round
+  constexpr int NT = kSelThreads, EPT = kSelEPT, ROUND = kSelRound;
+  extern __shared__ float stage[];
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t sh_scan[NW];
+  __shared__ uint32_t sh_scan[NT / 64];
   __shared__ uint32_t res[2];
-  __shared__ unsigned long long cnt[SUPER * NW];
-  __shared__ unsigned long long sh_scan64[NW];
+  __shared__ uint32_t sh_mm[2 * (NT / 64)];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int seg = blockIdx.x;
@@ -384,57 +430,176 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
   }
   const float* I = imp + tab.score_off[seg];
   float* P = pooled + tab.score_off[seg];
-  const int radius = pool_kernel / 2;
+  const int radius = RADIUS >= 0 ? RADIUS : pool_kernel / 2;
+  const bool is_max = pool_mode != SLKV_POOL_AVG;
+  const float fill = is_max ? -INFINITY : 0.f;
   const float inv_p = 1.f / (float)pool_kernel;
-  for (int j = tid; j < m; j += NT) P[j] = pooled_at(I, j, m, radius, pool_mode, inv_p);
-  // each thread re-reads only what it wrote itself (same j -> thread map in every sweep)
-  uint32_t need_eq;
-  auto key_at = [&](int64_t j, uint32_t& key) {
-    key = __float_as_uint(P[j]);                   // scores are >= 0: the bit pattern is monotone
-    return true;
+  const int rounds = (m + ROUND - 1) / ROUND;
+  const bool multi = rounds > 1;
+
+  float p[EPT];                                    // pooled scores of this thread in the current round
+
+  // pooled scores of round r from the importance array
+  auto pool_round = [&](int r) {
+    const int base = r * ROUND;
+#pragma unroll
+    for (int c = 0; c < EPT; ++c) {
+      const int s = c * NT + tid, j = base - radius + s;
+      stage[pad_idx(s)] = (j >= 0 && j < m) ? I[j] : fill;
+    }
+    if (tid < 2 * radius) {
+      const int s = ROUND + tid, j = base - radius + s;
+      stage[pad_idx(s)] = (j >= 0 && j < m) ? I[j] : fill;
+    }
+    __syncthreads();
+    if (RADIUS >= 0) {
+      float v[EPT + 2 * (RADIUS >= 0 ? RADIUS : 0)];
+#pragma unroll
+      for (int e = 0; e < EPT + 2 * RADIUS; ++e) v[e] = stage[pad_idx(EPT * tid + e)];
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        float a = v[e];
+#pragma unroll
+        for (int t = 1; t <= 2 * RADIUS; ++t) a = is_max ? fmaxf(a, v[e + t]) : a + v[e + t];
+        p[e] = is_max ? a : a * inv_p;
+      }
+    } else {
+#pragma unroll 1
+      for (int e = 0; e < EPT; ++e) {
+        float a = stage[pad_idx(EPT * tid + e)];
+        for (int t = 1; t <= 2 * radius; ++t) {
+          const float x = stage[pad_idx(EPT * tid + e + t)];
+          a = is_max ? fmaxf(a, x) : a + x;
+        }
+        p[e] = is_max ? a : a * inv_p;
+      }
+    }
+    __syncthreads();
   };
-  const uint32_t tau = block_radix_select<NT>(key_at, (int64_t)m, (uint32_t)kk, hist, sh_scan, res, &need_eq);
+  // pooled scores of round r read back from the pooled array (histories longer than one round)
+  auto reload_round = [&](int r) {
+    const int base = r * ROUND;
+#pragma unroll
+    for (int c = 0; c < EPT; ++c) {
+      const int s = c * NT + tid, j = base + s;
+      stage[pad_idx(s)] = j < m ? P[j] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) p[e] = stage[pad_idx(EPT * tid + e)];
+    __syncthreads();
+  };
+
+  // pass 1: pooled scores, their range, and (if asked or needed later) the pooled array
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+  for (int r = 0; r < rounds; ++r) {
+    pool_round(r);
+    const int j0 = r * ROUND + EPT * tid;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (j0 + e < m) {
+        const uint32_t key = __float_as_uint(p[e]);
+        kmin = min(kmin, key);
+        kmax = max(kmax, key);
+        if (write_pooled || multi) P[j0 + e] = p[e];
+      }
+    }
+  }
+#pragma unroll
+  for (int dlt = 32; dlt > 0; dlt >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, dlt, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, dlt, 64));
+  }
+  if (lane == 0) {
+    sh_mm[wv] = kmin;
+    sh_mm[NT / 64 + wv] = kmax;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) {
+    kmin = min(kmin, sh_mm[i]);
+    kmax = max(kmax, sh_mm[NT / 64 + i]);
+  }
+  if (multi) __threadfence_block();                // the pooled array is re-read by other threads below
+  __syncthreads();
+
+  // radix select on (key - lo) >> shift
+  uint32_t lo = kmin, hi = kmax, k = (uint32_t)kk;
+  while (true) {
+    const uint32_t span1 = hi - lo;
+    const int nbits = span1 ? 32 - __clz(span1) : 0;
+    const int shift = nbits > 11 ? nbits - 11 : 0;
+    for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
+    __syncthreads();
+    for (int r = 0; r < rounds; ++r) {
+      if (multi) reload_round(r);
+      const int j0 = r * ROUND + EPT * tid;
+      uint32_t cur = 0xffffffffu, cnt = 0;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t key = __float_as_uint(p[e]);
+        if (j0 + e < m && key >= lo && key <= hi) {
+          const uint32_t b = (key - lo) >> shift;
+          if (b == cur) {
+            cnt += 1;
+          } else {
+            if (cnt) atomicAdd(&hist[cur], cnt);
+            cur = b;
+            cnt = 1;
+          }
+        }
+      }
+      if (cnt) atomicAdd(&hist[cur], cnt);
+    }
+    __syncthreads();
+    select_bin<NT>(hist, k, sh_scan, res);
+    const uint32_t bsel = res[0];
+    k = res[1];
+    __syncthreads();
+    lo = lo + (bsel << shift);
+    hi = min(hi, lo + ((1u << shift) - 1u));
+    if (shift == 0) break;
+  }
+  const uint32_t tau = lo, need_eq = k;
 
   // ordered compaction: position = (#greater before) + min(#equal before, need_eq)
-  unsigned long long carry = 0;                    // (equal << 32) | greater, over finished rounds
-  for (int base0 = 0; base0 < m; base0 += SUPER * NT) {
-    const int tiles = min(SUPER, (m - base0 + NT - 1) / NT);
-    for (int t = 0; t < tiles; ++t) {
-      const int j = base0 + t * NT + tid;
-      const uint32_t key = j < m ? __float_as_uint(P[j]) : 0u;
-      const unsigned long long bg = __ballot(j < m && key > tau);
-      const unsigned long long be = __ballot(j < m && key == tau);
-      if (lane == 0) cnt[t * NW + wv] = ((unsigned long long)__popcll(be) << 32) | (unsigned long long)__popcll(bg);
+  uint32_t carry_g = 0, carry_e = 0;
+  for (int r = 0; r < rounds; ++r) {
+    if (multi) reload_round(r);
+    const int j0 = r * ROUND + EPT * tid;
+    uint32_t cg = 0, ce = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const uint32_t key = __float_as_uint(p[e]);
+      if (j0 + e < m) {
+        cg += key > tau ? 1u : 0u;
+        ce += key == tau ? 1u : 0u;
+      }
     }
+    const uint32_t packed = (ce << 16) | cg;       // a round holds at most 32768 of either
+    const uint32_t incl = block_incl_scan<NT, uint32_t>(packed, sh_scan);
+    if (tid == NT - 1) res[0] = incl;
     __syncthreads();
-    // exclusive scan of cnt[0 .. tiles*NW) in (tile, wave) order, two entries per thread
-    {
-      const int e0 = 2 * tid, e1 = 2 * tid + 1, ne = tiles * NW;
-      const unsigned long long a = e0 < ne ? cnt[e0] : 0ull, b = e1 < ne ? cnt[e1] : 0ull;
-      const unsigned long long incl = block_incl_scan<NT, unsigned long long>(a + b, sh_scan64);
-      if (e0 < ne) cnt[e0] = carry + incl - a - b;
-      if (e1 < ne) cnt[e1] = carry + incl - b;
-      __syncthreads();
+    const uint32_t tot = res[0];
+    const uint32_t excl = incl - packed;
+    uint32_t g_before = carry_g + (excl & 0xffffu), e_before = carry_e + (excl >> 16);
+    if (cg | ce) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t key = __float_as_uint(p[e]);
+        if (j0 + e < m) {
+          if (key > tau) {
+            out[g_before + min(e_before, need_eq)] = j0 + e;
+            g_before += 1;
+          } else if (key == tau) {
+            if (e_before < need_eq) out[g_before + e_before] = j0 + e;
+            e_before += 1;
+          }
+        }
+      }
     }
-    unsigned long long last = 0;
-    for (int t = 0; t < tiles; ++t) {
-      const int j = base0 + t * NT + tid;
-      const uint32_t key = j < m ? __float_as_uint(P[j]) : 0u;
-      const bool g = j < m && key > tau, e = j < m && key == tau;
-      const unsigned long long bg = __ballot(g), be = __ballot(e);
-      const unsigned long long lower = (1ull << lane) - 1ull;
-      const unsigned long long basev = cnt[t * NW + wv];
-      const uint32_t g_before = (uint32_t)(basev & 0xffffffffull) + (uint32_t)__popcll(bg & lower);
-      const uint32_t e_before = (uint32_t)(basev >> 32) + (uint32_t)__popcll(be & lower);
-      if (g || (e && e_before < need_eq)) out[g_before + min(e_before, need_eq)] = j;
-      if (t == tiles - 1 && wv == NW - 1)
-        last = basev + (((unsigned long long)__popcll(be) << 32) | (unsigned long long)__popcll(bg));
-    }
-    // totals after this round: value held by the last wave; broadcast through LDS
-    __syncthreads();
-    if (tid == NT - 1) cnt[0] = last;
-    __syncthreads();
-    carry = cnt[0];
+    carry_g += tot & 0xffffu;
+    carry_e += tot >> 16;
     __syncthreads();
   }
 }
@@ -542,6 +707,35 @@ static void launch_score(int pass, int grid, hipStream_t st, const SegTable& tab
   }
 }
 
+template <int RADIUS>
+static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, const slkv_layer_desc* d,
+                                  bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
+                                  int64_t* d_out_offsets, int is_last) {
+  static bool attr_set = false;   // LDS above 64 KB per workgroup has to be requested once per kernel
+  const size_t lds = (size_t)kSelStageFloats * sizeof(float);
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((select_kernel<RADIUS>), dim3(ns), dim3(kSelThreads), lds, st, tab, d->w, d->pool_kernel, d->pool,
+                     (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+  return hipSuccess;
+}
+
+static hipError_t launch_select(int ns, hipStream_t st, const SegTable& tab, const slkv_layer_desc* d, bool write_pooled,
+                                const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets, int is_last) {
+  const int radius = d->pool == SLKV_POOL_NONE ? 0 : d->pool_kernel / 2;
+  switch (radius) {
+    case 0: return launch_select_r<0>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+    case 1: return launch_select_r<1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+    case 2: return launch_select_r<2>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+    case 3: return launch_select_r<3>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+    default: return launch_select_r<-1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+  }
+}
+
 }  // namespace slkv
 
 using namespace slkv;
@@ -571,6 +765,11 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
   for (const void* ptr : ptrs)
     if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(SLKV_ERR_BAD_ARG, "device pointer %p not 16-byte aligned", ptr);
   if ((int64_t)desc->B * desc->Hq * desc->w >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "B*Hq*w >= 2^31");
+  for (int b = 0; b < desc->B; ++b) {   // the kernels address a sequence's keys with 32-bit byte offsets
+    const int64_t n = desc->h_cu_seqlens[b + 1] - desc->h_cu_seqlens[b];
+    if (n * desc->k_stride_tok * (desc->dtype == SLKV_BF16 ? 2 : 4) >= (int64_t(1) << 31))
+      return fail(SLKV_ERR_UNSUPPORTED, "sequence %d spans 2 GiB or more of K", b);
+  }
   Plan p;
   make_plan(desc, p);
   if (workspace_bytes < p.total_bytes)
@@ -628,14 +827,28 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
       tab.chunk_begin[i] = chunks;
     }
     if (chunks > 0) {
-      launch_score(1, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
-      hipLaunchKernelGGL(combine_kernel, dim3(ns), dim3(256), 0, st, tab, p.Rpad, part, lse);
-      launch_score(2, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+      {
+        ScopedKernelTimer tm(SLKV_K_SCORE_STATS, st);
+        launch_score(1, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+      }
+      {
+        ScopedKernelTimer tm(SLKV_K_COMBINE, st);
+        hipLaunchKernelGGL(combine_kernel, dim3((p.Rpad + 15) / 16, ns), dim3(256), 0, st, tab, p.Rpad, part, lse);
+      }
+      {
+        ScopedKernelTimer tm(SLKV_K_SCORE_ACCUM, st);
+        launch_score(2, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+      }
     }
-    hipLaunchKernelGGL(select_kernel, dim3(ns), dim3(kSelThreads), 0, st, tab, desc->w, desc->pool_kernel, desc->pool,
-                       imp, pooled, d_kept_idx, d_out_offsets, (int)(s0 + ns == S));
+    {
+      ScopedKernelTimer tm(SLKV_K_SELECT, st);
+      hipError_t se = launch_select(ns, st, tab, desc, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets,
+                                    (int)(s0 + ns == S));
+      if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
+    }
     const int64_t rows = (int64_t)tab.out_off[ns] - tab.out_off[0];
     if (rows > 0) {
+      ScopedKernelTimer tm(SLKV_K_GATHER, st);
       const int64_t threads = rows * lanes_per_row;
       hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, lanes_per_row,
                          elt, (const unsigned char*)d_k, (const unsigned char*)d_v, desc->k_stride_tok,

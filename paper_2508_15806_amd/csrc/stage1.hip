@@ -216,14 +216,20 @@ extern "C" slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t 
   hipStream_t st = (hipStream_t)hip_stream;
   double* cells = (double*)d_workspace;
   const bool resident = (n % 4 == 0) && n <= (int64_t)kS1Threads * kS1Resident;
+  {
+  ScopedKernelTimer tm(SLKV_K_ROW_CELLS, st);
   if (resident)
     hipLaunchKernelGGL(row_cells_kernel<true>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, n, needle_start,
                        needle_len, topk, cells);
   else
     hipLaunchKernelGGL(row_cells_kernel<false>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, n, needle_start,
                        needle_len, topk, cells);
+  }
   const int heads = L * H;
-  hipLaunchKernelGGL(head_reduce_kernel, dim3((heads + 127) / 128), dim3(128), 0, st, cells, heads, T, d_acc, d_scores);
+  {
+    ScopedKernelTimer tm(SLKV_K_HEAD_REDUCE, st);
+    hipLaunchKernelGGL(head_reduce_kernel, dim3((heads + 127) / 128), dim3(128), 0, st, cells, heads, T, d_acc, d_scores);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
   return SLKV_OK;

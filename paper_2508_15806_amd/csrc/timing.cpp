@@ -1,0 +1,76 @@
+// Optional per-kernel timing with HIP events (slkv_profile_begin / slkv_profile_end).
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+#include <vector>
+
+#include "slkv_internal.h"
+
+namespace {
+struct Rec {
+  int id;
+  hipEvent_t a, b;
+};
+std::mutex g_mu;
+bool g_on = false;
+std::vector<Rec> g_pool;   // events created by slkv_profile_begin
+size_t g_used = 0;
+}  // namespace
+
+namespace slkv {
+
+ScopedKernelTimer::ScopedKernelTimer(int id, void* stream) : slot_(-1), stream_(stream) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_on || g_used >= g_pool.size()) return;
+  slot_ = (int)g_used++;
+  g_pool[slot_].id = id;
+  (void)hipEventRecord(g_pool[slot_].a, (hipStream_t)stream_);
+}
+
+ScopedKernelTimer::~ScopedKernelTimer() {
+  if (slot_ < 0) return;
+  std::lock_guard<std::mutex> lk(g_mu);
+  (void)hipEventRecord(g_pool[slot_].b, (hipStream_t)stream_);
+}
+
+}  // namespace slkv
+
+using namespace slkv;
+
+extern "C" slkv_status slkv_profile_begin(int32_t max_records) {
+  clear_error();
+  if (max_records < 1 || max_records > (1 << 20)) return fail(SLKV_ERR_BAD_ARG, "max_records outside 1..2^20");
+  std::lock_guard<std::mutex> lk(g_mu);
+  while ((int)g_pool.size() < max_records) {
+    Rec r;
+    r.id = -1;
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess)
+      return fail(SLKV_ERR_HIP, "hipEventCreate failed");
+    g_pool.push_back(r);
+  }
+  g_used = 0;
+  g_on = true;
+  return SLKV_OK;
+}
+
+extern "C" slkv_status slkv_profile_end(slkv_kernel_time* h_records, int32_t capacity, int32_t* count) {
+  clear_error();
+  if (!count) return fail(SLKV_ERR_NULL, "count is NULL");
+  std::lock_guard<std::mutex> lk(g_mu);
+  g_on = false;
+  int n = 0;
+  for (size_t i = 0; i < g_used; ++i) {
+    if (hipEventSynchronize(g_pool[i].b) != hipSuccess) return fail(SLKV_ERR_HIP, "hipEventSynchronize failed");
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_pool[i].a, g_pool[i].b) != hipSuccess)
+      return fail(SLKV_ERR_HIP, "hipEventElapsedTime failed");
+    if (h_records && n < capacity) {
+      h_records[n].kernel = g_pool[i].id;
+      h_records[n].ms = ms;
+    }
+    ++n;
+  }
+  *count = n;
+  g_used = 0;
+  return SLKV_OK;
+}
