@@ -393,6 +393,8 @@ constexpr int kSelEPT = 32;
 constexpr int kSelRound = kSelThreads * kSelEPT;
 constexpr int kSelHaloMax = kMaxPool / 2;
 constexpr int kSelStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * kSelHaloMax) >> 5) + 8;
+constexpr int kSelRankMax = 256;       // lists up to this length are ranked by direct counting
+constexpr int kSelCandidates = 3072;   // scores of one first-level digit that the LDS list can hold
 
 __device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
 
@@ -442,26 +444,47 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
   // pooled scores of round r from the importance array
   auto pool_round = [&](int r) {
     const int base = r * ROUND;
+    // all loads first (clamped addresses, so none depends on a branch), then the LDS writes
+    float ld[EPT + 1];
+#pragma unroll
+    for (int c = 0; c <= EPT; ++c) {
+      const int j = base - radius + (c < EPT ? c * NT + tid : ROUND + min(tid, 2 * radius));
+      ld[c] = I[min(max(j, 0), m - 1)];
+    }
 #pragma unroll
     for (int c = 0; c < EPT; ++c) {
       const int s = c * NT + tid, j = base - radius + s;
-      stage[pad_idx(s)] = (j >= 0 && j < m) ? I[j] : fill;
+      stage[pad_idx(s)] = (j >= 0 && j < m) ? ld[c] : fill;
     }
     if (tid < 2 * radius) {
       const int s = ROUND + tid, j = base - radius + s;
-      stage[pad_idx(s)] = (j >= 0 && j < m) ? I[j] : fill;
+      stage[pad_idx(s)] = (j >= 0 && j < m) ? ld[EPT] : fill;
     }
     __syncthreads();
     if (RADIUS >= 0) {
-      float v[EPT + 2 * (RADIUS >= 0 ? RADIUS : 0)];
+      constexpr int RR = RADIUS >= 0 ? RADIUS : 0;
+      float v[EPT + 2 * RR + 2];
 #pragma unroll
-      for (int e = 0; e < EPT + 2 * RADIUS; ++e) v[e] = stage[pad_idx(EPT * tid + e)];
+      for (int e = 0; e < EPT + 2 * RR; ++e) v[e] = stage[pad_idx(EPT * tid + e)];
+      v[EPT + 2 * RR] = v[EPT + 2 * RR + 1] = fill;
+      if (is_max) {
+        // window maxima by doubling: widths 2 and 4, then two overlapping pieces cover 2*RR+1
+        float w2[EPT + 2 * RR + 1], w4[EPT + 2 * RR];
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        float a = v[e];
+        for (int e = 0; e < EPT + 2 * RR + 1; ++e) w2[e] = fmaxf(v[e], v[e + 1]);
 #pragma unroll
-        for (int t = 1; t <= 2 * RADIUS; ++t) a = is_max ? fmaxf(a, v[e + t]) : a + v[e + t];
-        p[e] = is_max ? a : a * inv_p;
+        for (int e = 0; e < EPT + 2 * RR - 1; ++e) w4[e] = fmaxf(w2[e], w2[e + 2]);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+          p[e] = RR == 0 ? v[e] : RR == 1 ? fmaxf(w2[e], v[e + 2]) : RR == 2 ? fmaxf(w4[e], v[e + 4]) : fmaxf(w4[e], w4[e + 3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          float a = v[e];
+#pragma unroll
+          for (int t = 1; t <= 2 * RR; ++t) a += v[e + t];
+          p[e] = a * inv_p;
+        }
       }
     } else {
 #pragma unroll 1
@@ -479,30 +502,41 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
   // pooled scores of round r read back from the pooled array (histories longer than one round)
   auto reload_round = [&](int r) {
     const int base = r * ROUND;
+    float ld[EPT];
 #pragma unroll
-    for (int c = 0; c < EPT; ++c) {
-      const int s = c * NT + tid, j = base + s;
-      stage[pad_idx(s)] = j < m ? P[j] : 0.f;
-    }
+    for (int c = 0; c < EPT; ++c) ld[c] = P[min(base + c * NT + tid, m - 1)];
+#pragma unroll
+    for (int c = 0; c < EPT; ++c) stage[pad_idx(c * NT + tid)] = ld[c];
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < EPT; ++e) p[e] = stage[pad_idx(EPT * tid + e)];
     __syncthreads();
   };
 
+  // Keys of the current round: bit patterns of the pooled scores (>= 0, so monotone); positions
+  // past the end of the history get a key above every score.
+  uint32_t key[EPT];
+  auto make_keys = [&](int r) {
+    const int j0 = r * ROUND + EPT * tid;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) key[e] = j0 + e < m ? __float_as_uint(p[e]) : 0xffffffffu;
+  };
+
   // pass 1: pooled scores, their range, and (if asked or needed later) the pooled array
   uint32_t kmin = 0xffffffffu, kmax = 0u;
   for (int r = 0; r < rounds; ++r) {
     pool_round(r);
+    make_keys(r);
     const int j0 = r * ROUND + EPT * tid;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      if (j0 + e < m) {
-        const uint32_t key = __float_as_uint(p[e]);
-        kmin = min(kmin, key);
-        kmax = max(kmax, key);
-        if (write_pooled || multi) P[j0 + e] = p[e];
-      }
+      kmin = min(kmin, key[e]);
+      if (key[e] != 0xffffffffu) kmax = max(kmax, key[e]);
+    }
+    if (write_pooled || multi) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        if (j0 + e < m) P[j0 + e] = p[e];
     }
   }
 #pragma unroll
@@ -523,80 +557,121 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
   if (multi) __threadfence_block();                // the pooled array is re-read by other threads below
   __syncthreads();
 
-  // radix select on (key - lo) >> shift
+  // Radix select on (key - lo) >> shift.  The first level histograms every score; the scores
+  // of the chosen digit are then collected in LDS (the staging array) and the remaining
+  // levels work on that list.  If the list would not fit, the levels sweep all scores again.
   uint32_t lo = kmin, hi = kmax, k = (uint32_t)kk;
-  while (true) {
+  uint32_t* cand = reinterpret_cast<uint32_t*>(stage + kSelStageFloats);   // after the staging area
+  constexpr uint32_t kCandCap = kSelCandidates;
+  bool use_list = false;
+  uint32_t ncand = 0;
+  for (int level = 0;; ++level) {
     const uint32_t span1 = hi - lo;
     const int nbits = span1 ? 32 - __clz(span1) : 0;
     const int shift = nbits > 11 ? nbits - 11 : 0;
-    for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
-    __syncthreads();
-    for (int r = 0; r < rounds; ++r) {
-      if (multi) reload_round(r);
-      const int j0 = r * ROUND + EPT * tid;
-      uint32_t cur = 0xffffffffu, cnt = 0;
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        const uint32_t key = __float_as_uint(p[e]);
-        if (j0 + e < m && key >= lo && key <= hi) {
-          const uint32_t b = (key - lo) >> shift;
-          if (b == cur) {
-            cnt += 1;
-          } else {
-            if (cnt) atomicAdd(&hist[cur], cnt);
-            cur = b;
-            cnt = 1;
-          }
+    if (use_list && ncand <= kSelRankMax) {
+      // short list: the k-th largest by counting, for each entry, the entries above it
+      if (tid < ncand) {
+        const uint32_t kv = cand[tid];
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t i = 0; i < ncand; ++i) {
+          const uint32_t o = cand[i];
+          gt += o > kv ? 1u : 0u;
+          ge += o >= kv ? 1u : 0u;
+        }
+        if (gt < k && k <= ge) {   // every thread holding the k-th largest value writes the same pair
+          res[0] = kv;
+          res[1] = k - gt;
         }
       }
-      if (cnt) atomicAdd(&hist[cur], cnt);
+      __syncthreads();
+      lo = res[0];
+      k = res[1];
+      __syncthreads();
+      break;
+    }
+    for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
+    __syncthreads();
+    if (use_list) {
+      for (uint32_t i = tid; i < ncand; i += NT) {
+        const uint32_t kv = cand[i];
+        if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
+      }
+    } else {
+      for (int r = 0; r < rounds; ++r) {
+        if (multi) {
+          reload_round(r);
+          make_keys(r);
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+          if (key[e] >= lo && key[e] <= hi) atomicAdd(&hist[(key[e] - lo) >> shift], 1u);
+      }
     }
     __syncthreads();
     select_bin<NT>(hist, k, sh_scan, res);
-    const uint32_t bsel = res[0];
+    const uint32_t bsel = res[0], cnt_sel = hist[bsel];
     k = res[1];
     __syncthreads();
     lo = lo + (bsel << shift);
     hi = min(hi, lo + ((1u << shift) - 1u));
     if (shift == 0) break;
+    if (level == 0 && cnt_sel <= kCandCap) {
+      // collect the scores of the chosen digit (their order does not matter for counting)
+      if (tid == 0) res[0] = 0;
+      __syncthreads();
+      for (int r = 0; r < rounds; ++r) {
+        if (multi) {
+          reload_round(r);
+          make_keys(r);
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+          if (key[e] >= lo && key[e] <= hi) cand[atomicAdd(&res[0], 1u)] = key[e];
+      }
+      __syncthreads();
+      ncand = res[0];
+      use_list = true;
+      __syncthreads();
+    }
   }
   const uint32_t tau = lo, need_eq = k;
 
   // ordered compaction: position = (#greater before) + min(#equal before, need_eq)
   uint32_t carry_g = 0, carry_e = 0;
   for (int r = 0; r < rounds; ++r) {
-    if (multi) reload_round(r);
+    if (multi) {
+      reload_round(r);
+      make_keys(r);
+    }
     const int j0 = r * ROUND + EPT * tid;
-    uint32_t cg = 0, ce = 0;
+    uint32_t gmask = 0, emask = 0;                 // bit e: element e is above / equal to the threshold
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      const uint32_t key = __float_as_uint(p[e]);
-      if (j0 + e < m) {
-        cg += key > tau ? 1u : 0u;
-        ce += key == tau ? 1u : 0u;
-      }
+      gmask |= (key[e] > tau && key[e] != 0xffffffffu) ? (1u << e) : 0u;
+      emask |= key[e] == tau ? (1u << e) : 0u;
     }
+    const uint32_t cg = __popc(gmask), ce = __popc(emask);
     const uint32_t packed = (ce << 16) | cg;       // a round holds at most 32768 of either
     const uint32_t incl = block_incl_scan<NT, uint32_t>(packed, sh_scan);
     if (tid == NT - 1) res[0] = incl;
     __syncthreads();
     const uint32_t tot = res[0];
     const uint32_t excl = incl - packed;
-    uint32_t g_before = carry_g + (excl & 0xffffu), e_before = carry_e + (excl >> 16);
-    if (cg | ce) {
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        const uint32_t key = __float_as_uint(p[e]);
-        if (j0 + e < m) {
-          if (key > tau) {
-            out[g_before + min(e_before, need_eq)] = j0 + e;
-            g_before += 1;
-          } else if (key == tau) {
-            if (e_before < need_eq) out[g_before + e_before] = j0 + e;
-            e_before += 1;
-          }
-        }
-      }
+    const uint32_t g_before = carry_g + (excl & 0xffffu), e_before = carry_e + (excl >> 16);
+    // ties are taken in position order: this thread keeps its first `take` equal elements
+    uint32_t take = 0;
+    if (e_before < need_eq) take = (need_eq - e_before) < ce ? (need_eq - e_before) : ce;
+    uint32_t sel = gmask;
+    for (uint32_t em = emask; take > 0; --take) {
+      sel |= em & (0u - em);                       // lowest set bit
+      em &= em - 1u;
+    }
+    uint32_t pos = g_before + (e_before < need_eq ? e_before : need_eq);
+    while (sel) {
+      const int e = __ffs(sel) - 1;
+      out[pos++] = j0 + e;
+      sel &= sel - 1u;
     }
     carry_g += tot & 0xffffu;
     carry_e += tot >> 16;
@@ -712,7 +787,7 @@ static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, c
                                   bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
                                   int64_t* d_out_offsets, int is_last) {
   static bool attr_set = false;   // LDS above 64 KB per workgroup has to be requested once per kernel
-  const size_t lds = (size_t)kSelStageFloats * sizeof(float);
+  const size_t lds = (size_t)(kSelStageFloats + kSelCandidates) * sizeof(float);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
