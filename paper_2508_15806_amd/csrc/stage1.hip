@@ -12,13 +12,15 @@ namespace slkv {
 
 constexpr int kS1Threads = 256;
 constexpr int kS1Resident = 64;   // elements per thread held in registers (rows up to 16384)
+constexpr int kS1Cand = 512;      // weights at or above the bound that the exact ranking can hold
 
-// One workgroup per row.  RESIDENT: the row (n % 4 == 0, n <= 256*64) is read once with 16-byte
-// loads and kept in registers; otherwise every sweep re-reads it.
+// One workgroup per row.  RESIDENT: the row (n % 4 == 0, n <= 256*64, K <= 64) is read once with
+// 16-byte loads and kept in registers for the small-K path; the general radix select re-reads
+// the row in every sweep.
 // cells[row] = (WO, WD, WS, Wide).
 template <bool RESIDENT>
-__global__ __launch_bounds__(kS1Threads) void row_cells_kernel(const float* __restrict__ rows, int64_t n,
-                                                               int64_t needle_start, int32_t needle_len, int32_t topk,
+__global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* __restrict__ rows, int32_t n,
+                                                                  int32_t needle_start, int32_t needle_len, int32_t topk,
                                                                double* __restrict__ cells) {
   constexpr int NT = kS1Threads;
   __shared__ uint32_t hist[kHistBins];
@@ -29,45 +31,117 @@ __global__ __launch_bounds__(kS1Threads) void row_cells_kernel(const float* __re
 
   const int tid = threadIdx.x;
   const float* W = rows + (int64_t)blockIdx.x * n;
-  const int64_t ne = needle_start + needle_len;
+  const int32_t ne = needle_start + needle_len;
 
   float v[RESIDENT ? kS1Resident : 1];
   // element e of the resident copy: position ((e/4)*NT + tid)*4 + e%4
   if (RESIDENT) {
 #pragma unroll
     for (int i = 0; i < kS1Resident / 4; ++i) {
-      const int64_t j = ((int64_t)i * NT + tid) * 4;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (j < n) x = *reinterpret_cast<const float4*>(W + j);
+      const int32_t j = (i * NT + tid) * 4;
+      const float4 x = *reinterpret_cast<const float4*>(W + (j < n ? j : n - 4));   // past the end: ignored below
       v[4 * i + 0] = x.x;
       v[4 * i + 1] = x.y;
       v[4 * i + 2] = x.z;
       v[4 * i + 3] = x.w;
     }
   }
-  auto pos_of = [&](int e) -> int64_t { return ((int64_t)(e >> 2) * NT + tid) * 4 + (e & 3); };
+  auto pos_of = [&](int e) -> int32_t { return ((e >> 2) * NT + tid) * 4 + (e & 3); };
 
-  // sweep helper: f(position, value) over the thread's elements
+  // sweep helper of the general path: f(position, value) over the row, re-read from memory
   auto sweep = [&](auto f) {
-    if (RESIDENT) {
-#pragma unroll
-      for (int e = 0; e < kS1Resident; ++e) {
-        const int64_t j = pos_of(e);
-        if (j < n) f(j, v[e]);
-      }
-    } else {
-      for (int64_t j = tid; j < n; j += NT) f(j, W[j]);
-    }
+    for (int32_t j = tid; j < n; j += NT) f(j, W[j]);
   };
 
   // row sum and needle sum in double
   double tot = 0.0, tnw = 0.0;
-  sweep([&](int64_t j, float x) {
-    tot += (double)x;
-    if (j >= needle_start && j < ne) tnw += (double)x;
-  });
+  if (RESIDENT) {
+#pragma unroll
+    for (int e = 0; e < kS1Resident; ++e)
+      if (pos_of(e) < n) tot += (double)v[e];
+  } else {
+    sweep([&](int32_t, float x) { tot += (double)x; });
+  }
+  for (int32_t j = needle_start + tid; j < ne; j += NT) tnw += (double)W[j];
   tot = block_sum<NT, double>(tot, sh_d);
   tnw = block_sum<NT, double>(tnw, sh_d);
+
+  // Small K on a resident row: a lower bound of the K-th largest weight comes from the lane
+  // maxima of each wave (K distinct elements); the few weights at or above the bound are
+  // collected in LDS and ranked exactly (larger first, equal weights by lower position).
+  if (RESIDENT && topk <= kWave) {
+    __shared__ float sh_bound[NT / 64];
+    __shared__ uint32_t cand_cnt;
+    __shared__ float cand_val[kS1Cand];
+    __shared__ int32_t cand_pos[kS1Cand];
+    __shared__ float slot_val[kWave];
+    __shared__ int32_t slot_in[kWave];
+    const int lane = tid & 63, wv = tid >> 6;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < kS1Resident; ++e)
+      if (pos_of(e) < n) mx = fmaxf(mx, v[e]);
+    // rank of this lane's maximum among the 64 of its wave (ties by lower lane)
+    int rk = 0;
+    for (int l = 0; l < kWave; ++l) {
+      const float o = __shfl(mx, l, kWave);
+      rk += (o > mx || (o == mx && l < lane)) ? 1 : 0;
+    }
+    const unsigned long long hit = __ballot(rk == topk - 1);
+    const float bound_w = __shfl(mx, __ffsll((long long)hit) - 1, kWave);
+    if (lane == 0) sh_bound[wv] = bound_w;
+    if (tid == 0) cand_cnt = 0;
+    __syncthreads();
+    float bound = sh_bound[0];
+#pragma unroll
+    for (int i = 1; i < NT / 64; ++i) bound = fmaxf(bound, sh_bound[i]);
+#pragma unroll
+    for (int e = 0; e < kS1Resident; ++e) {
+      const int32_t j = pos_of(e);
+      if (j < n && v[e] >= bound) {
+        const uint32_t slot = atomicAdd(&cand_cnt, 1u);
+        if (slot < (uint32_t)kS1Cand) {
+          cand_val[slot] = v[e];
+          cand_pos[slot] = j;
+        }
+      }
+    }
+    __syncthreads();
+    const uint32_t nc = cand_cnt;
+    if (nc <= (uint32_t)kS1Cand) {
+      for (uint32_t i = tid; i < nc; i += NT) {
+        const float x = cand_val[i];
+        const int32_t px = cand_pos[i];
+        int r = 0;
+        for (uint32_t o = 0; o < nc; ++o) {
+          const float y = cand_val[o];
+          r += (y > x || (y == x && cand_pos[o] < px)) ? 1 : 0;
+        }
+        if (r < topk) {
+          slot_val[r] = x;
+          slot_in[r] = (px >= needle_start && px < ne) ? 1 : 0;
+        }
+      }
+      __syncthreads();
+      if (wv == 0) {
+        const bool on = lane < topk;
+        const double x = on ? (double)slot_val[lane] : 0.0;
+        const bool inn = on && slot_in[lane];
+        const double WO = wave_sum<double>(inn ? x : 0.0);
+        const double WD = wave_sum<double>(inn ? 0.0 : x);
+        if (lane == 0) {
+          const double WS = fmax(0.0, tnw - WO);
+          double* c = cells + (int64_t)blockIdx.x * 4;
+          c[0] = WO;
+          c[1] = WD;
+          c[2] = WS;
+          c[3] = tot - WO - WD - WS;
+        }
+      }
+      return;
+    }
+    __syncthreads();   // too many ties at the bound: fall through to the general select
+  }
 
   // K-th largest weight: three histogram levels over the order-preserving key
   uint32_t prefix = 0, k = (uint32_t)topk;
@@ -77,7 +151,7 @@ __global__ __launch_bounds__(kS1Threads) void row_cells_kernel(const float* __re
     const int bits = level == 2 ? 10 : 11;
     for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
     __syncthreads();
-    sweep([&](int64_t, float x) {
+    sweep([&](int32_t, float x) {
       const uint32_t key = float_key(x);
       if (level == 0 || (key >> (shift + bits)) == prefix) atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1u);
     });
@@ -94,7 +168,7 @@ __global__ __launch_bounds__(kS1Threads) void row_cells_kernel(const float* __re
   double wo = 0.0, wd = 0.0;
   uint32_t eq_all = 0, eq_needle = 0;
   float tau_val = 0.f;
-  sweep([&](int64_t j, float x) {
+  sweep([&](int32_t j, float x) {
     const uint32_t key = float_key(x);
     const bool inn = j >= needle_start && j < ne;
     if (key > tau) {
@@ -132,7 +206,7 @@ __global__ __launch_bounds__(kS1Threads) void row_cells_kernel(const float* __re
       const int bits = level == 2 ? 10 : 11;
       for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
       __syncthreads();
-      sweep([&](int64_t j, float x) {
+      sweep([&](int32_t j, float x) {
         if (float_key(x) != tau) return;
         const uint32_t key = ~(uint32_t)j;
         if (level == 0 || (key >> (shift + bits)) == p2) atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1u);
@@ -143,9 +217,9 @@ __global__ __launch_bounds__(kS1Threads) void row_cells_kernel(const float* __re
       k2 = res[1];
       __syncthreads();
     }
-    const int64_t last_pos = (int64_t)(~p2);
+    const int32_t last_pos = (int32_t)(~p2);
     uint32_t cntn = 0;
-    sweep([&](int64_t j, float x) {
+    sweep([&](int32_t j, float x) {
       if (float_key(x) == tau && j <= last_pos && j >= needle_start && j < ne) cntn += 1;
     });
     take_needle = block_sum<NT, uint32_t>(cntn, sh_u);
@@ -215,15 +289,15 @@ extern "C" slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t 
 
   hipStream_t st = (hipStream_t)hip_stream;
   double* cells = (double*)d_workspace;
-  const bool resident = (n % 4 == 0) && n <= (int64_t)kS1Threads * kS1Resident;
+  const bool resident = (n % 4 == 0) && n >= 4 && n <= (int64_t)kS1Threads * kS1Resident && topk <= kWave;
   {
   ScopedKernelTimer tm(SLKV_K_ROW_CELLS, st);
   if (resident)
-    hipLaunchKernelGGL(row_cells_kernel<true>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, n, needle_start,
-                       needle_len, topk, cells);
+    hipLaunchKernelGGL(row_cells_kernel<true>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, (int32_t)n,
+                       (int32_t)needle_start, needle_len, topk, cells);
   else
-    hipLaunchKernelGGL(row_cells_kernel<false>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, n, needle_start,
-                       needle_len, topk, cells);
+    hipLaunchKernelGGL(row_cells_kernel<false>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, (int32_t)n,
+                       (int32_t)needle_start, needle_len, topk, cells);
   }
   const int heads = L * H;
   {
