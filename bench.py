@@ -23,8 +23,8 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/); None until measured for the current kernels.
-MEASURED_TRAFFIC_BYTES = None
+# (profiles/compress_layer_c3_avg256_rocprofv3.md): scoring pass 1, 63776 KiB read + 947 KiB written.
+MEASURED_TRAFFIC_BYTES = 66.3e6
 
 
 def parse():
@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-stage1", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 256 MiB device copy (reference for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -118,6 +120,13 @@ def main():
         step(args.warmup + i)
     torch.cuda.synchronize()
     recs = B.slkv_profile_end(nrec)
+    # what an event pair reads with nothing between its two records (subtracted below)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+    for a_, b_ in pairs:
+        a_.record()
+        b_.record()
+    torch.cuda.synchronize()
+    pair_ms = float(np.median([a_.elapsed_time(b_) for a_, b_ in pairs]))
     per_kernel = {}
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
@@ -127,12 +136,12 @@ def main():
     # launches of the scoring kernels only happen on layers with ranked heads
     ranked_flops = [x[0] for x in work if x[3] > 0]
     flops_launch = float(np.mean(ranked_flops)) if ranked_flops else 0.0
-    dom_ms = kernel_ms.get(dom, float("nan"))
+    dom_ms = kernel_ms.get(dom, float("nan")) - pair_ms
     achieved_tflops = flops_launch / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved_tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5),
+                "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5), "empty_event_pair_ms": round(pair_ms, 5),
                 "flops_per_launch": flops_launch}
 
     out = {
@@ -152,6 +161,14 @@ def main():
                   "kernel_launches_per_step": kernel_launches,
                   "kernel_sum_ms": round(sum(kernel_ms[k] * kernel_launches[k] for k in kernel_ms), 5)},
     }
+
+    if args.calibration_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                  # 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     # other budgets of the sweep (same inputs, shorter loops)
     sweep = {}
