@@ -81,20 +81,25 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
 #pragma unroll
     for (int e = 0; e < kS1Resident; ++e)
       if (pos_of(e) < n) mx = fmaxf(mx, v[e]);
-    // rank of this lane's maximum among the 64 of its wave (ties by lower lane)
-    int rk = 0;
-    for (int l = 0; l < kWave; ++l) {
-      const float o = __shfl(mx, l, kWave);
-      rk += (o > mx || (o == mx && l < lane)) ? 1 : 0;
+    // Each wave finds the ceil(K/4)-th largest of its 64 lane maxima (bisection on the key bits
+    // with ballots).  At least K weights are >= the smallest of the four values, so that value
+    // bounds the K-th largest weight from below.
+    const int want = (topk + NT / 64 - 1) / (NT / 64);
+    const uint32_t mkey = float_key(mx);
+    uint32_t tkey = 0;
+    for (int b = 31; b >= 0; --b) {
+      const uint32_t trial = tkey | (1u << b);
+      if (__popcll(__ballot(mkey >= trial)) >= want) tkey = trial;
     }
-    const unsigned long long hit = __ballot(rk == topk - 1);
+    // tkey is now the want-th largest key of the wave; recover its float from a lane holding it
+    const unsigned long long hit = __ballot(mkey == tkey);
     const float bound_w = __shfl(mx, __ffsll((long long)hit) - 1, kWave);
     if (lane == 0) sh_bound[wv] = bound_w;
     if (tid == 0) cand_cnt = 0;
     __syncthreads();
     float bound = sh_bound[0];
 #pragma unroll
-    for (int i = 1; i < NT / 64; ++i) bound = fmaxf(bound, sh_bound[i]);
+    for (int i = 1; i < NT / 64; ++i) bound = fminf(bound, sh_bound[i]);
 #pragma unroll
     for (int e = 0; e < kS1Resident; ++e) {
       const int32_t j = pos_of(e);
