@@ -388,6 +388,17 @@ __global__ __launch_bounds__(256) void combine_kernel(const SegTable tab, int Rp
 // The k-th largest pooled score is found by a radix select whose digits are taken relative to
 // the segment's own [min, max] of score bit patterns (scores are >= 0, so the bit pattern is
 // monotone): 11 bits per level over the remaining range, at most three levels.
+constexpr int kInlineGatherRows = 1024;   // segments up to this many kept rows are gathered by select_kernel
+
+struct GatherArgs {
+  const unsigned char* k;
+  const unsigned char* v;
+  unsigned char* k_out;
+  unsigned char* v_out;
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;   // elements
+  int lanes_per_row, elt_bytes;
+};
+
 constexpr int kSelThreads = 1024;
 constexpr int kSelEPT = 32;
 constexpr int kSelRound = kSelThreads * kSelEPT;
@@ -402,7 +413,8 @@ template <int RADIUS>   // pooling radius known at compile time (0..3), or -1: a
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab, int w, int pool_kernel, int pool_mode,
                                                              int write_pooled, const float* __restrict__ imp,
                                                              float* __restrict__ pooled, int32_t* __restrict__ kept_idx,
-                                                             int64_t* __restrict__ d_out_offsets, int is_last_group) {
+                                                             int64_t* __restrict__ d_out_offsets, int is_last_group,
+                                                             const GatherArgs ga) {
   constexpr int NT = kSelThreads, EPT = kSelEPT, ROUND = kSelRound;
   extern __shared__ float stage[];
   __shared__ uint32_t hist[kHistBins];
@@ -419,17 +431,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
     d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
     if (is_last_group && seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
   }
+  const int m = n - w;
+  bool ranked = false;
   if (kk < 0) {                                    // whole segment kept
     for (int j = tid; j < n; j += NT) out[j] = j;
-    return;
+  } else {
+    for (int j = tid; j < w; j += NT) out[kk + j] = m + j;
+    if (kk >= m) {
+      for (int j = tid; j < m; j += NT) out[j] = j;
+    } else if (kk > 0) {
+      ranked = true;
+    }
   }
-  const int m = n - w;
-  for (int j = tid; j < w; j += NT) out[kk + j] = m + j;
-  if (kk == 0) return;
-  if (kk >= m) {
-    for (int j = tid; j < m; j += NT) out[j] = j;
-    return;
-  }
+  if (ranked) {
   const float* I = imp + tab.score_off[seg];
   float* P = pooled + tab.score_off[seg];
   const int radius = RADIUS >= 0 ? RADIUS : pool_kernel / 2;
@@ -677,29 +691,46 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
     carry_e += tot >> 16;
     __syncthreads();
   }
+  }  // ranked
+
+  // Small segments copy their K/V rows here (saves the gather launch); larger ones are left
+  // to gather_kernel, which skips the segments handled here.
+  const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
+  if (kept > 0 && kept <= kInlineGatherRows) {
+    __threadfence_block();
+    __syncthreads();                                // the positions written above are visible to the block
+    const int64_t tok0 = tab.tok_begin[seg], h = tab.head[seg], row0 = tab.out_off[seg];
+    const int pieces = kept * ga.lanes_per_row;
+    for (int idx = tid; idx < pieces; idx += NT) {
+      const int row = idx / ga.lanes_per_row, c = idx % ga.lanes_per_row;
+      const int64_t tok = tok0 + out[row];
+      const uint4 kv = *reinterpret_cast<const uint4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + c * 16);
+      const uint4 vv = *reinterpret_cast<const uint4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + c * 16);
+      const int64_t o = ((row0 + row) * ga.lanes_per_row + c) * 16;
+      *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
+      *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
+    }
+  }
 }
 
 // Copies kept rows of K and V (bit copies) into the packed output; one 16-byte lane per piece.
-__global__ __launch_bounds__(256) void gather_kernel(const SegTable tab, int lanes_per_row, int elt_bytes,
-                                                     const unsigned char* __restrict__ k,
-                                                     const unsigned char* __restrict__ v, int64_t k_stride_tok,
-                                                     int64_t k_stride_head, int64_t v_stride_tok, int64_t v_stride_head,
-                                                     unsigned char* __restrict__ k_out, unsigned char* __restrict__ v_out,
+__global__ __launch_bounds__(256) void gather_kernel(const SegTable tab, const GatherArgs ga,
                                                      const int32_t* __restrict__ kept_idx) {
   const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t rel = g / lanes_per_row;
-  const int c = (int)(g % lanes_per_row);
+  const int64_t rel = g / ga.lanes_per_row;
+  const int c = (int)(g % ga.lanes_per_row);
   const int64_t row0 = tab.out_off[0], row1 = tab.out_off[tab.nseg];
   const int64_t row = row0 + rel;
   if (row >= row1) return;
   const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
+  if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by select_kernel
   const int64_t tok = (int64_t)tab.tok_begin[seg] + kept_idx[row];
   const int64_t h = tab.head[seg];
-  const int64_t row_bytes = (int64_t)lanes_per_row * 16;
-  const uint4 kv = *reinterpret_cast<const uint4*>(k + (h * k_stride_head + tok * k_stride_tok) * elt_bytes + c * 16);
-  const uint4 vv = *reinterpret_cast<const uint4*>(v + (h * v_stride_head + tok * v_stride_tok) * elt_bytes + c * 16);
-  *reinterpret_cast<uint4*>(k_out + row * row_bytes + c * 16) = kv;
-  *reinterpret_cast<uint4*>(v_out + row * row_bytes + c * 16) = vv;
+  const uint4 kv = *reinterpret_cast<const uint4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + c * 16);
+  const uint4 vv = *reinterpret_cast<const uint4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + c * 16);
+  const int64_t o = (row * ga.lanes_per_row + c) * 16;
+  *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
+  *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -785,7 +816,7 @@ static void launch_score(int pass, int grid, hipStream_t st, const SegTable& tab
 template <int RADIUS>
 static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, const slkv_layer_desc* d,
                                   bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
-                                  int64_t* d_out_offsets, int is_last) {
+                                  int64_t* d_out_offsets, int is_last, const GatherArgs& ga) {
   static bool attr_set = false;   // LDS above 64 KB per workgroup has to be requested once per kernel
   const size_t lds = (size_t)(kSelStageFloats + kSelCandidates) * sizeof(float);
   if (!attr_set) {
@@ -795,19 +826,20 @@ static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, c
     attr_set = true;
   }
   hipLaunchKernelGGL((select_kernel<RADIUS>), dim3(ns), dim3(kSelThreads), lds, st, tab, d->w, d->pool_kernel, d->pool,
-                     (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+                     (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
   return hipSuccess;
 }
 
 static hipError_t launch_select(int ns, hipStream_t st, const SegTable& tab, const slkv_layer_desc* d, bool write_pooled,
-                                const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets, int is_last) {
+                                const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets, int is_last,
+                                const GatherArgs& ga) {
   const int radius = d->pool == SLKV_POOL_NONE ? 0 : d->pool_kernel / 2;
   switch (radius) {
-    case 0: return launch_select_r<0>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
-    case 1: return launch_select_r<1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
-    case 2: return launch_select_r<2>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
-    case 3: return launch_select_r<3>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
-    default: return launch_select_r<-1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last);
+    case 0: return launch_select_r<0>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 1: return launch_select_r<1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 2: return launch_select_r<2>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 3: return launch_select_r<3>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    default: return launch_select_r<-1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
   }
 }
 
@@ -868,6 +900,18 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
   const int elt = desc->dtype == SLKV_BF16 ? 2 : 4;
   const int lanes_per_row = desc->d * elt / 16;
 
+  GatherArgs ga;
+  ga.k = (const unsigned char*)d_k;
+  ga.v = (const unsigned char*)d_v;
+  ga.k_out = (unsigned char*)d_k_out;
+  ga.v_out = (unsigned char*)d_v_out;
+  ga.k_stride_tok = desc->k_stride_tok;
+  ga.k_stride_head = desc->k_stride_head;
+  ga.v_stride_tok = desc->v_stride_tok;
+  ga.v_stride_head = desc->v_stride_head;
+  ga.lanes_per_row = lanes_per_row;
+  ga.elt_bytes = elt;
+
   const int S = desc->B * desc->Hkv;
   int64_t out_run = 0;
   for (int s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
@@ -918,17 +962,16 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
     {
       ScopedKernelTimer tm(SLKV_K_SELECT, st);
       hipError_t se = launch_select(ns, st, tab, desc, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets,
-                                    (int)(s0 + ns == S));
+                                    (int)(s0 + ns == S), ga);
       if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
     }
     const int64_t rows = (int64_t)tab.out_off[ns] - tab.out_off[0];
-    if (rows > 0) {
+    bool any_large = false;
+    for (int i = 0; i < ns; ++i) any_large |= tab.out_off[i + 1] - tab.out_off[i] > kInlineGatherRows;
+    if (any_large) {
       ScopedKernelTimer tm(SLKV_K_GATHER, st);
       const int64_t threads = rows * lanes_per_row;
-      hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, lanes_per_row,
-                         elt, (const unsigned char*)d_k, (const unsigned char*)d_v, desc->k_stride_tok,
-                         desc->k_stride_head, desc->v_stride_tok, desc->v_stride_head, (unsigned char*)d_k_out,
-                         (unsigned char*)d_v_out, d_kept_idx);
+      hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
