@@ -97,6 +97,28 @@ def test_heavy_ties_are_cut_by_lowest_position():
     check(lay, np.array([200, 700], dtype=np.int32), require_exact=True)
 
 
+@pytest.mark.parametrize("n,protos,budget", [(5016, 5, 1500), (9016, 2, 2000), (9016, 2, 6000), (70008, 2, 40000),
+                                             (3016, 1, 3015)])
+def test_tie_groups_of_every_size(n, protos, budget):
+    # History keys drawn from a few prototypes, no pooling: the scores form `protos` groups of equal
+    # values, so the threshold falls inside a tie group of hundreds to tens of thousands of entries
+    # (in-LDS candidate list, list overflow, several compaction rounds).
+    w = 16
+    lay = wl.make_layer((109, n, protos), [n], 2, 1, 64, w, dtype="bf16")
+    m = n - w
+    lay.k[:, :m, :] = lay.k[:, :protos, :][:, np.arange(m) % protos, :]
+    rep = check(lay, np.array([budget], dtype=np.int32), 1, B.SLKV_POOL_NONE, require_exact=True)
+    assert rep["ranked"] == 1
+
+
+def test_inline_and_separate_gather_in_one_launch():
+    # kept-row counts on both sides of the limit up to which the selection kernel copies rows itself
+    lay = wl.make_layer((110,), [3000, 1500, 40], 8, 4, 128, 16, dtype="bf16", bias_frac=0.05)
+    check(lay, np.array([1024, 1025, 16, 2900], dtype=np.int32))
+    lay = wl.make_layer((111,), [2100], 4, 2, 64, 8, dtype="f32", bias_frac=0.05)
+    check(lay, np.array([1024, 1500], dtype=np.int32))
+
+
 def test_many_segments_span_several_launch_groups():
     lens = [150 + 7 * i for i in range(40)]                        # 40 sequences x 2 heads = 80 segments
     lay = wl.make_layer((107,), lens, 4, 2, 64, 8, dtype="bf16", bias_frac=0.05)

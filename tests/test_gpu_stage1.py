@@ -37,9 +37,10 @@ def test_config4_shape_rows_resident():
     np.testing.assert_allclose(acc[..., :4].sum(-1), 16.0, rtol=1e-6)
 
 
-@pytest.mark.parametrize("n,topk", [(64, 1), (1000, 32), (5003, 100), (4096, 4096), (20000, 17), (70001, 64)])
+@pytest.mark.parametrize("n,topk", [(4, 1), (8, 8), (64, 1), (1000, 32), (5003, 100), (4096, 4096), (4096, 65), (16384, 64),
+                                    (16388, 64), (20000, 17), (70001, 64)])
 def test_row_lengths_and_k(n, topk):
-    nr = wl.config4(L=1, H=3, T=5, n=n, needle_len=min(32, n // 2), seed_extra=n)
+    nr = wl.config4(L=1, H=3, T=5, n=n, needle_len=max(1, min(32, n // 2)), seed_extra=n)
     check(nr.rows, nr.needle_start, nr.needle_len, topk)
 
 
