@@ -14,9 +14,9 @@ constexpr int kS1Threads = 256;
 constexpr int kS1Resident = 64;   // elements per thread held in registers (rows up to 16384)
 constexpr int kS1Cand = 512;      // weights at or above the bound that the exact ranking can hold
 
-// One workgroup per row.  RESIDENT: the row (n % 4 == 0, n <= 256*64, K <= 64) is read once with
-// 16-byte loads and kept in registers for the small-K path; the general radix select re-reads
-// the row in every sweep.
+// One workgroup per row.  RESIDENT (n % 4 == 0, n <= 256*64, K <= 64): the row is read once with
+// 16-byte loads and stays in registers for the small-K path.  The general radix select reads
+// the row from memory in every sweep.
 // cells[row] = (WO, WD, WS, Wide).
 template <bool RESIDENT>
 __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* __restrict__ rows, int32_t n,
@@ -33,98 +33,155 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
   const float* W = rows + (int64_t)blockIdx.x * n;
   const int32_t ne = needle_start + needle_len;
 
-  float v[RESIDENT ? kS1Resident : 1];
-  // element e of the resident copy: position ((e/4)*NT + tid)*4 + e%4
-  if (RESIDENT) {
-#pragma unroll
-    for (int i = 0; i < kS1Resident / 4; ++i) {
-      const int32_t j = (i * NT + tid) * 4;
-      const float4 x = *reinterpret_cast<const float4*>(W + (j < n ? j : n - 4));   // past the end: ignored below
-      v[4 * i + 0] = x.x;
-      v[4 * i + 1] = x.y;
-      v[4 * i + 2] = x.z;
-      v[4 * i + 3] = x.w;
-    }
-  }
-  auto pos_of = [&](int e) -> int32_t { return ((e >> 2) * NT + tid) * 4 + (e & 3); };
-
   // sweep helper of the general path: f(position, value) over the row, re-read from memory
   auto sweep = [&](auto f) {
     for (int32_t j = tid; j < n; j += NT) f(j, W[j]);
   };
 
-  // row sum and needle sum in double
-  double tot = 0.0, tnw = 0.0;
+  double tot = 0.0, tnw = 0.0;           // row sum and needle sum, in double
   if (RESIDENT) {
-#pragma unroll
-    for (int e = 0; e < kS1Resident; ++e)
-      if (pos_of(e) < n) tot += (double)v[e];
-  } else {
-    sweep([&](int32_t, float x) { tot += (double)x; });
-  }
-  for (int32_t j = needle_start + tid; j < ne; j += NT) tnw += (double)W[j];
-  tot = block_sum<NT, double>(tot, sh_d);
-  tnw = block_sum<NT, double>(tnw, sh_d);
-
-  // Small K on a resident row: a lower bound of the K-th largest weight comes from the lane
-  // maxima of each wave (K distinct elements); the few weights at or above the bound are
-  // collected in LDS and ranked exactly (larger first, equal weights by lower position).
-  if (RESIDENT && topk <= kWave) {
-    __shared__ float sh_bound[NT / 64];
-    __shared__ uint32_t cand_cnt;
+    // Small K on a row held in registers.  A lower bound of the K-th largest weight comes from
+    // the lane maxima of each wave (K distinct elements); the few weights at or above the bound
+    // are collected in LDS and ranked exactly (larger first, equal weights by lower position).
+    constexpr int NW = NT / kWave;
+    constexpr int kWaveCand = kS1Cand / NW;
+    __shared__ double sh_tot[NW], sh_tnw[NW];
+    __shared__ float sh_bound[NW];
+    __shared__ uint32_t sh_cnt[NW];
     __shared__ float cand_val[kS1Cand];
     __shared__ int32_t cand_pos[kS1Cand];
+    __shared__ uint32_t cand_rank[kS1Cand];
     __shared__ float slot_val[kWave];
     __shared__ int32_t slot_in[kWave];
     const int lane = tid & 63, wv = tid >> 6;
+    const int32_t ngroups = n >> 2;      // n % 4 == 0: the row is whole 16-byte groups
+
+    // group i of this thread: positions 4 * (i * NT + tid) .. + 3; all loads are issued first
+    const float4* W4 = reinterpret_cast<const float4*>(W);
+    float4 v[kS1Resident / 4];
+#pragma unroll
+    for (int i = 0; i < kS1Resident / 4; ++i) {
+      const int32_t g = i * NT + tid;
+      v[i] = W4[g < ngroups ? g : ngroups - 1];   // past the end: loaded again, never used
+    }
+    const int32_t jn = needle_start + tid;
+    const float nd = W[jn < ne ? jn : needle_start];
+
     float mx = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < kS1Resident; ++e)
-      if (pos_of(e) < n) mx = fmaxf(mx, v[e]);
-    // Each wave finds the ceil(K/4)-th largest of its 64 lane maxima (bisection on the key bits
-    // with ballots).  At least K weights are >= the smallest of the four values, so that value
-    // bounds the K-th largest weight from below.
-    const int want = (topk + NT / 64 - 1) / (NT / 64);
-    const uint32_t mkey = float_key(mx);
-    uint32_t tkey = 0;
-    for (int b = 31; b >= 0; --b) {
-      const uint32_t trial = tkey | (1u << b);
-      if (__popcll(__ballot(mkey >= trial)) >= want) tkey = trial;
+    for (int i = 0; i < kS1Resident / 4; ++i) {
+      if (i * NT + tid < ngroups) {
+        tot += (double)v[i].x;
+        tot += (double)v[i].y;
+        tot += (double)v[i].z;
+        tot += (double)v[i].w;
+        mx = fmaxf(fmaxf(mx, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+      }
     }
-    // tkey is now the want-th largest key of the wave; recover its float from a lane holding it
-    const unsigned long long hit = __ballot(mkey == tkey);
-    const float bound_w = __shfl(mx, __ffsll((long long)hit) - 1, kWave);
-    if (lane == 0) sh_bound[wv] = bound_w;
-    if (tid == 0) cand_cnt = 0;
+    if (jn < ne) tnw = (double)nd;
+    for (int32_t j = jn + NT; j < ne; j += NT) tnw += (double)W[j];
+    tot = wave_sum<double>(tot);
+    tnw = wave_sum<double>(tnw);
+
+    // Each wave finds a value at or below the ceil(K/4)-th largest of its 64 lane maxima
+    // (bisection on the upper 20 bits of the order-preserving key, with ballots).  At least K
+    // weights are >= the smallest of the four values, so it bounds the K-th largest from below.
+    const uint32_t want = (uint32_t)(topk + NW - 1) / NW;
+    const uint32_t mkey = tid < ngroups ? float_key(mx) : 0u;   // lanes without data never count
+    uint32_t tkey = 0;
+#pragma unroll
+    for (int b = 31; b >= 12; --b) {
+      const uint32_t trial = tkey | (1u << b);
+      if ((uint32_t)__popcll(__ballot(mkey >= trial)) >= want) tkey = trial;
+    }
+    // the float whose key is tkey (low bits cleared: not above the value found); 0 keys: -inf
+    const float bound_w = tkey == 0 ? -INFINITY
+                                    : __uint_as_float((tkey & 0x80000000u) ? (tkey ^ 0x80000000u) : ~tkey);
+    if (lane == 0) {
+      sh_tot[wv] = tot;
+      sh_tnw[wv] = tnw;
+      sh_bound[wv] = bound_w;
+    }
+    for (int i = tid; i < kS1Cand; i += NT) cand_rank[i] = 0;
     __syncthreads();
+    tot = sh_tot[0];
+    tnw = sh_tnw[0];
     float bound = sh_bound[0];
 #pragma unroll
-    for (int i = 1; i < NT / 64; ++i) bound = fminf(bound, sh_bound[i]);
+    for (int i = 1; i < NW; ++i) {
+      tot += sh_tot[i];
+      tnw += sh_tnw[i];
+      bound = fminf(bound, sh_bound[i]);
+    }
+
+    // Candidates of this wave go to its own part of the list; the slot of a lane is the number
+    // of candidates found so far plus the candidates of the same element in lower lanes.
+    uint32_t base = 0;                   // wave-uniform
+    float* my_val = cand_val + wv * kWaveCand;
+    int32_t* my_pos = cand_pos + wv * kWaveCand;
 #pragma unroll
-    for (int e = 0; e < kS1Resident; ++e) {
-      const int32_t j = pos_of(e);
-      if (j < n && v[e] >= bound) {
-        const uint32_t slot = atomicAdd(&cand_cnt, 1u);
-        if (slot < (uint32_t)kS1Cand) {
-          cand_val[slot] = v[e];
-          cand_pos[slot] = j;
+    for (int i = 0; i < kS1Resident / 4; ++i) {
+      const int32_t g = i * NT + tid;
+      const float bnd = g < ngroups ? bound : INFINITY;
+      const float x[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool is = x[c] >= bnd;
+        const unsigned long long mask = __ballot(is);
+        if (mask) {
+          const uint32_t slot = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+          if (is && slot < (uint32_t)kWaveCand) {
+            my_val[slot] = x[c];
+            my_pos[slot] = 4 * g + c;
+          }
+          base += (uint32_t)__popcll(mask);
         }
       }
     }
+    if (lane == 0) sh_cnt[wv] = base;
     __syncthreads();
-    const uint32_t nc = cand_cnt;
-    if (nc <= (uint32_t)kS1Cand) {
-      for (uint32_t i = tid; i < nc; i += NT) {
-        const float x = cand_val[i];
-        const int32_t px = cand_pos[i];
-        int r = 0;
-        for (uint32_t o = 0; o < nc; ++o) {
-          const float y = cand_val[o];
-          r += (y > x || (y == x && cand_pos[o] < px)) ? 1 : 0;
+    uint32_t cnt[NW], nc = 0;
+    bool fits = true;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      cnt[i] = sh_cnt[i];
+      nc += cnt[i];
+      fits = fits && cnt[i] <= (uint32_t)kWaveCand;
+    }
+    if (fits && nc >= (uint32_t)topk) {
+      // rank of a candidate = number of candidates ahead of it; wave wv counts those of its own part
+      const uint32_t mine = cnt[wv];
+      for (uint32_t c0 = 0; c0 < nc; c0 += kWave) {
+        const uint32_t c = c0 + lane;    // candidate c in the order of the parts
+        uint32_t part = 0, idx = c;
+#pragma unroll
+        for (int i = 0; i < NW - 1; ++i)
+          if (part == (uint32_t)i && idx >= cnt[i]) {
+            idx -= cnt[i];
+            part = i + 1;
+          }
+        if (c < nc) {
+          const float x = cand_val[part * kWaveCand + idx];
+          const int32_t px = cand_pos[part * kWaveCand + idx];
+          uint32_t r = 0;
+          for (uint32_t o = 0; o < mine; ++o) {
+            const float y = my_val[o];
+            r += (y > x || (y == x && my_pos[o] < px)) ? 1u : 0u;
+          }
+          if (r) atomicAdd(&cand_rank[part * kWaveCand + idx], r);
         }
-        if (r < topk) {
-          slot_val[r] = x;
-          slot_in[r] = (px >= needle_start && px < ne) ? 1 : 0;
+      }
+      __syncthreads();
+      for (uint32_t c = tid; c < (uint32_t)kS1Cand; c += NT) {
+        const uint32_t part = c / kWaveCand, idx = c % kWaveCand;
+        if (idx < cnt[part]) {
+          const uint32_t r = cand_rank[c];
+          if (r < (uint32_t)topk) {
+            const int32_t px = cand_pos[c];
+            slot_val[r] = cand_val[c];
+            slot_in[r] = (px >= needle_start && px < ne) ? 1 : 0;
+          }
         }
       }
       __syncthreads();
@@ -145,7 +202,12 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
       }
       return;
     }
-    __syncthreads();   // too many ties at the bound: fall through to the general select
+    // too many ties at the bound: the general select below re-reads the row
+  } else {
+    sweep([&](int32_t, float x) { tot += (double)x; });
+    for (int32_t j = needle_start + tid; j < ne; j += NT) tnw += (double)W[j];
+    tot = block_sum<NT, double>(tot, sh_d);
+    tnw = block_sum<NT, double>(tnw, sh_d);
   }
 
   // K-th largest weight: three histogram levels over the order-preserving key
