@@ -50,9 +50,6 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
     __shared__ uint32_t sh_cnt[NW];
     __shared__ float cand_val[kS1Cand];
     __shared__ int32_t cand_pos[kS1Cand];
-    __shared__ uint32_t cand_rank[kS1Cand];
-    __shared__ float slot_val[kWave];
-    __shared__ int32_t slot_in[kWave];
     const int lane = tid & 63, wv = tid >> 6;
     const int32_t ngroups = n >> 2;      // n % 4 == 0: the row is whole 16-byte groups
 
@@ -102,7 +99,6 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
       sh_tnw[wv] = tnw;
       sh_bound[wv] = bound_w;
     }
-    for (int i = tid; i < kS1Cand; i += NT) cand_rank[i] = 0;
     __syncthreads();
     tot = sh_tot[0];
     tnw = sh_tnw[0];
@@ -150,10 +146,13 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
       fits = fits && cnt[i] <= (uint32_t)kWaveCand;
     }
     if (fits && nc >= (uint32_t)topk) {
-      // rank of a candidate = number of candidates ahead of it; wave wv counts those of its own part
-      const uint32_t mine = cnt[wv];
-      for (uint32_t c0 = 0; c0 < nc; c0 += kWave) {
-        const uint32_t c = c0 + lane;    // candidate c in the order of the parts
+      // A candidate belongs to T_k if fewer than K candidates are ahead of it (larger, or equal
+      // at a lower position).  Candidate c (in the order of the parts) is counted by thread c.
+      // Up to 64 candidates, the usual case, are handled by the first wave alone.
+      const bool one_wave = nc <= (uint32_t)kWave;
+      if (one_wave && wv != 0) return;
+      double wo = 0.0, wd = 0.0;
+      for (uint32_t c = tid; c < nc; c += NT) {
         uint32_t part = 0, idx = c;
 #pragma unroll
         for (int i = 0; i < NW - 1; ++i)
@@ -161,44 +160,34 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
             idx -= cnt[i];
             part = i + 1;
           }
-        if (c < nc) {
-          const float x = cand_val[part * kWaveCand + idx];
-          const int32_t px = cand_pos[part * kWaveCand + idx];
-          uint32_t r = 0;
-          for (uint32_t o = 0; o < mine; ++o) {
-            const float y = my_val[o];
-            r += (y > x || (y == x && my_pos[o] < px)) ? 1u : 0u;
+        const float x = cand_val[part * kWaveCand + idx];
+        const int32_t px = cand_pos[part * kWaveCand + idx];
+        uint32_t ahead = 0;
+#pragma unroll
+        for (int q = 0; q < NW; ++q)
+          for (uint32_t o = 0; o < cnt[q]; ++o) {
+            const float y = cand_val[q * kWaveCand + o];
+            const int32_t py = cand_pos[q * kWaveCand + o];
+            ahead += (y > x || (y == x && py < px)) ? 1u : 0u;
           }
-          if (r) atomicAdd(&cand_rank[part * kWaveCand + idx], r);
+        if (ahead < (uint32_t)topk) {
+          if (px >= needle_start && px < ne) wo += (double)x; else wd += (double)x;
         }
       }
-      __syncthreads();
-      for (uint32_t c = tid; c < (uint32_t)kS1Cand; c += NT) {
-        const uint32_t part = c / kWaveCand, idx = c % kWaveCand;
-        if (idx < cnt[part]) {
-          const uint32_t r = cand_rank[c];
-          if (r < (uint32_t)topk) {
-            const int32_t px = cand_pos[c];
-            slot_val[r] = cand_val[c];
-            slot_in[r] = (px >= needle_start && px < ne) ? 1 : 0;
-          }
-        }
+      if (one_wave) {
+        wo = wave_sum<double>(wo);
+        wd = wave_sum<double>(wd);
+      } else {
+        wo = block_sum<NT, double>(wo, sh_d);
+        wd = block_sum<NT, double>(wd, sh_d);
       }
-      __syncthreads();
-      if (wv == 0) {
-        const bool on = lane < topk;
-        const double x = on ? (double)slot_val[lane] : 0.0;
-        const bool inn = on && slot_in[lane];
-        const double WO = wave_sum<double>(inn ? x : 0.0);
-        const double WD = wave_sum<double>(inn ? 0.0 : x);
-        if (lane == 0) {
-          const double WS = fmax(0.0, tnw - WO);
-          double* c = cells + (int64_t)blockIdx.x * 4;
-          c[0] = WO;
-          c[1] = WD;
-          c[2] = WS;
-          c[3] = tot - WO - WD - WS;
-        }
+      if (tid == 0) {
+        const double WS = fmax(0.0, tnw - wo);
+        double* c = cells + (int64_t)blockIdx.x * 4;
+        c[0] = wo;
+        c[1] = wd;
+        c[2] = WS;
+        c[3] = tot - wo - wd - WS;
       }
       return;
     }
