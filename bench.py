@@ -109,6 +109,16 @@ def main():
     ms_step = ms_total / args.steps
     tokens_per_s = n / (ms_step * 1e-3)
 
+    # per-step latency distribution: one event pair per step (each pair adds its own record cost)
+    nlat = min(args.steps, 128)
+    lat_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nlat)]
+    for i in range(nlat):
+        lat_ev[i][0].record()
+        step(args.warmup + i)
+        lat_ev[i][1].record()
+    torch.cuda.synchronize()
+    lat = np.array([a_.elapsed_time(b_) for a_, b_ in lat_ev])
+
     work = [layer_work((args.warmup + i) % NL) for i in range(args.steps)]
     flops_step = float(np.mean([x[0] for x in work]))
     bytes_step = float(np.mean([x[1] for x in work]))
@@ -142,7 +152,10 @@ def main():
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5), "empty_event_pair_ms": round(pair_ms, 5),
-                "flops_per_launch": flops_launch}
+                "flops_per_launch": flops_launch,
+                # the same launch against the HBM roof (K of the ranked heads read once per pass)
+                "hbm_GBs": round(MEASURED_TRAFFIC_BYTES / (dom_ms * 1e-3) / 1e9, 1) if dom_ms > 0 else 0.0,
+                "hbm_frac": round(MEASURED_TRAFFIC_BYTES / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if dom_ms > 0 else 0.0}
 
     out = {
         "metric": "prefix KV tokens compressed/sec per layer (1 GPU)",
@@ -157,6 +170,9 @@ def main():
         "layer": {"algorithmic_bytes": bytes_step, "hbm_GBs": round(bytes_step / (ms_step * 1e-3) / 1e9, 1),
                   "hbm_frac": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                   "one_pass_TFLOPs": round(flops_step / (ms_step * 1e-3) / 1e12, 2),
+                  "step_ms_event_pairs": {"median": round(float(np.median(lat)), 5),
+                                          "p10": round(float(np.percentile(lat, 10)), 5),
+                                          "p90": round(float(np.percentile(lat, 90)), 5), "n": int(nlat)},
                   "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
                   "kernel_launches_per_step": kernel_launches,
                   "kernel_sum_ms": round(sum(kernel_ms[k] * kernel_launches[k] for k in kernel_ms), 5)},

@@ -7,7 +7,8 @@ only the tests, the smoke check and the benchmark's CPU-baseline leg use it.
 
 Modules
   compress  - Stage 2b: window scoring, softmax importance, pooling, top-k,
-              gather (Eq. 2-4, Eq. 7-8, Algorithm 3).
+              gather (Eq. 2-4, Eq. 7-8, Algorithm 3), on a packed
+              prefill batch and on an already compacted cache.
   budgets   - Stage 2a: per-head capacities (Eq. 6, Algorithm 2).
   behavior  - Stage 1: WO / WD / WS counting and SF / LG / INF scores
               (Algorithm 1).
@@ -26,6 +27,7 @@ from .compress import (  # noqa: F401
     select_topk,
     compress_segment,
     compress_layer,
+    recompress_layer,
     kept_count,
 )
 from .budgets import allocate_budgets, allocate_budgets_literal, fixed_from_beta  # noqa: F401

@@ -150,3 +150,39 @@ def compress_layer(qwin, k, v, cu_seqlens, budgets, w, pool_kernel=7, pool_mode=
     v_out = np.concatenate([s["v_out"] for s in segs], axis=0)
     return dict(segments=segs, out_offsets=np.asarray(offs, dtype=np.int64),
                 k_out=k_out, v_out=v_out)
+
+
+def recompress_layer(qwin, k_rows, v_rows, in_offsets, budgets, w, pool_kernel=7, pool_mode=POOL_MAX,
+                     pos_in=None):
+    """Algorithm 3 applied to a cache that is already ragged (Section 3.4: the selection runs
+    whenever a head's cache length exceeds its capacity, so also on a compacted cache that has
+    grown during generation).
+
+    qwin: [B, Hq, w, d] queries of the latest w tokens; k_rows, v_rows: [rows, d] packed cache,
+    segment s = b*Hkv + h at rows in_offsets[s]..in_offsets[s+1] (its last w rows are the
+    window); budgets: [Hkv]; pos_in: optional [rows] original token position of every cached row.
+    Returns the dict of compress_layer plus pos_out (pos_in at the kept rows) when pos_in is given.
+    """
+    qwin = np.asarray(qwin)
+    B, Hq = qwin.shape[0], qwin.shape[1]
+    Hkv = len(budgets)
+    G = Hq // Hkv
+    segs = []
+    offs = [0]
+    pos_out = []
+    for b in range(B):
+        for h in range(Hkv):
+            s = b * Hkv + h
+            r0, r1 = int(in_offsets[s]), int(in_offsets[s + 1])
+            r = compress_segment(qwin[b, h * G:(h + 1) * G], k_rows[r0:r1], v_rows[r0:r1],
+                                 w, int(budgets[h]), pool_kernel, pool_mode)
+            segs.append(r)
+            offs.append(offs[-1] + r["kept_idx"].shape[0])
+            if pos_in is not None:
+                pos_out.append(np.asarray(pos_in)[r0 + r["kept_idx"]])
+    out = dict(segments=segs, out_offsets=np.asarray(offs, dtype=np.int64),
+               k_out=np.concatenate([s["k_out"] for s in segs], axis=0),
+               v_out=np.concatenate([s["v_out"] for s in segs], axis=0))
+    if pos_in is not None:
+        out["pos_out"] = np.concatenate(pos_out)
+    return out

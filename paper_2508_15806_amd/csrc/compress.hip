@@ -388,7 +388,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const SegTable tab, int Rp
 // The k-th largest pooled score is found by a radix select whose digits are taken relative to
 // the segment's own [min, max] of score bit patterns (scores are >= 0, so the bit pattern is
 // monotone): 11 bits per level over the remaining range, at most three levels.
-constexpr int kInlineGatherRows = 1024;   // segments up to this many kept rows are gathered by select_kernel
+constexpr int kInlineGatherRows = 256;    // segments up to this many kept rows are gathered by select_kernel
 
 struct GatherArgs {
   const unsigned char* k;

@@ -96,6 +96,68 @@ def make_layer(seed_key, seqlens, Hq, Hkv, d, w, dtype="bf16", bias_frac=0.0, bi
     return LayerInputs(dtype, B, Hq, Hkv, d, w, cu, q, k, v)
 
 
+class RaggedCache(object):
+    """A compacted cache that has grown: segment s = b*Hkv + h holds seg_lens[s] rows of K and V
+    (packed [rows, d]); pos_in is the original token position of every row (ascending inside a
+    segment, the last w rows of a segment being the newest tokens of its sequence)."""
+
+    def __init__(self, dtype, B, Hq, Hkv, d, w, in_offsets, qwin, k_rows, v_rows, pos_in):
+        self.dtype, self.B, self.Hq, self.Hkv, self.d, self.w = dtype, B, Hq, Hkv, d, w
+        self.in_offsets, self.qwin, self.k_rows, self.v_rows, self.pos_in = in_offsets, qwin, k_rows, v_rows, pos_in
+
+
+def make_ragged_cache(seed_key, seg_lens, B, Hq, Hkv, d, w, dtype="bf16", bias_frac=0.0, bias_sigma=4.0,
+                      seq_len=1 << 20):
+    """Rows ~ N(0,1) as in make_layer (same biased positions recipe, per segment).  seg_lens has
+    B*Hkv entries.  Positions: a sorted sample of [0, seq_len - w) for the history rows of the
+    segment, then the last w positions of the sequence."""
+    rng = _rng(*seed_key)
+    seg_lens = [int(x) for x in seg_lens]
+    assert len(seg_lens) == B * Hkv
+    offs = np.zeros(B * Hkv + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(seg_lens)
+    rows = int(offs[-1])
+    G = Hq // Hkv
+    q = rng.standard_normal((B, Hq, w, d), dtype=np.float32)
+    k = rng.standard_normal((rows, d), dtype=np.float32)
+    v = rng.standard_normal((rows, d), dtype=np.float32)
+    pos = np.zeros(rows, dtype=np.int32)
+    for s, n in enumerate(seg_lens):
+        b, h = divmod(s, Hkv)
+        r0 = int(offs[s])
+        m = max(n - w, 0)
+        if n > w:
+            pos[r0:r0 + m] = np.sort(rng.choice(seq_len - w, size=m, replace=False))
+            pos[r0 + m:r0 + n] = np.arange(seq_len - w, seq_len)
+        else:
+            pos[r0:r0 + n] = np.arange(seq_len - n, seq_len)
+        cnt = int(round(bias_frac * m))
+        if cnt > 0:
+            at = rng.choice(m, size=cnt, replace=False)
+            qh = rng.integers(0, G, size=cnt) + h * G
+            qi = rng.integers(0, w, size=cnt)
+            qv = q[b, qh, qi, :]
+            qv = qv / np.linalg.norm(qv, axis=1, keepdims=True)
+            k[r0 + at, :] += np.float32(bias_sigma) * qv
+    if dtype == "bf16":
+        q, k, v = to_bf16_bits(q), to_bf16_bits(k), to_bf16_bits(v)
+    elif dtype != "f32":
+        raise ValueError("dtype must be 'f32' or 'bf16'")
+    return RaggedCache(dtype, B, Hq, Hkv, d, w, offs, q, k, v, pos)
+
+
+def config6(head_lens, batch=32):
+    """Decode-time re-compression: `batch` sequences of Llama-3-8B shape (32q / 8kv heads, d 128,
+    window 64), bf16; head h of every sequence holds head_lens[h] cached rows (what its capacity
+    kept after prefill plus the tokens generated since; the caller computes the lengths)."""
+    head_lens = [int(x) for x in head_lens]
+    assert len(head_lens) == 8
+    rc = make_ragged_cache((BASE_SEED + 6, batch), head_lens * batch, batch, 32, 8, 128, 64, dtype="bf16",
+                           bias_frac=0.02, seq_len=32768 + 4096)
+    rc.meta = dict(name="c6", avg=256, fixed=16, pool=7)
+    return rc
+
+
 # ---------------------------------------------------------------- INF_sc maps
 
 def inf_uniform(seed_key, L, Hq):

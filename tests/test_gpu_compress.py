@@ -114,9 +114,9 @@ def test_tie_groups_of_every_size(n, protos, budget):
 def test_inline_and_separate_gather_in_one_launch():
     # kept-row counts on both sides of the limit up to which the selection kernel copies rows itself
     lay = wl.make_layer((110,), [3000, 1500, 40], 8, 4, 128, 16, dtype="bf16", bias_frac=0.05)
-    check(lay, np.array([1024, 1025, 16, 2900], dtype=np.int32))
+    check(lay, np.array([256, 257, 16, 2900], dtype=np.int32))
     lay = wl.make_layer((111,), [2100], 4, 2, 64, 8, dtype="f32", bias_frac=0.05)
-    check(lay, np.array([1024, 1500], dtype=np.int32))
+    check(lay, np.array([256, 1500], dtype=np.int32))
 
 
 def test_many_segments_span_several_launch_groups():
