@@ -159,6 +159,51 @@ slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin,
                                 int64_t out_capacity_rows,
                                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------ Stage 2b on a ragged cache
+ * Section 3.4 runs the selection whenever a head's cache length exceeds its capacity, which
+ * also happens during generation, when the cache is the compacted output of an earlier call
+ * plus the tokens appended since.  Input here is such a cache: segment s = b*Hkv + h owns the
+ * packed rows h_in_offsets[s] .. h_in_offsets[s+1] of d_k_in / d_v_in ([rows][d], rows
+ * contiguous), its length n_s differs from head to head, and its last w rows are the window
+ * (the latest w tokens, whose queries are d_qwin[b]).  Everything else is Algorithm 3 exactly
+ * as in slkv_compress_layer, with n_s in place of n_b.
+ */
+typedef struct {
+  uint32_t struct_size;        /* sizeof(slkv_ragged_desc) */
+  int32_t dtype;               /* slkv_dtype of Q, K, V */
+  int32_t B, Hq, Hkv, d, w;    /* as in slkv_layer_desc */
+  int32_t pool_kernel, pool;   /* as in slkv_layer_desc */
+  int32_t reserved;            /* 0 */
+  const int64_t* h_in_offsets; /* [B*Hkv+1] host: first input row of every segment, non-decreasing,
+                                  >= 0, last < 2^31 */
+  const int32_t* h_budgets;    /* [Hkv] host: capacities C_h >= 0 */
+} slkv_ragged_desc;
+
+/* Kept-row counts of slkv_recompress_layer (same outputs as slkv_compacted_sizes). */
+slkv_status slkv_recompress_sizes(const slkv_ragged_desc* desc, int64_t* h_out_offsets,
+                                  int64_t* total_kept);
+/* Device workspace slkv_recompress_layer needs for this descriptor. */
+slkv_status slkv_recompress_workspace_bytes(const slkv_ragged_desc* desc, size_t* bytes);
+
+/* d_qwin   [B][Hq][w][d] queries of the latest w tokens (device, read only)
+ * d_k_in, d_v_in [rows][d] packed cache (device, read only)
+ * d_pos_in  [rows] int32, may be NULL: original token position of every cached row
+ * d_k_out, d_v_out [total_kept][d] out; d_kept_idx [total_kept] int32 out: kept row numbers
+ *           inside the segment (ascending, the window last)
+ * d_pos_out [total_kept] int32 out, NULL exactly when d_pos_in is NULL: d_pos_in at the kept rows,
+ *           so that positions survive any number of compressions
+ * d_out_offsets [B*Hkv+1] int64 out, may be NULL
+ * d_importance, d_pooled: may be NULL.  fp32 [rows] each; segment s occupies n_s - w entries
+ *           starting at h_in_offsets[s] - h_in_offsets[0], written only when the segment is ranked.
+ * The outputs must not overlap the inputs.  Errors as slkv_compress_layer.
+ */
+slkv_status slkv_recompress_layer(const slkv_ragged_desc* desc, const void* d_qwin,
+                                  const void* d_k_in, const void* d_v_in, const int32_t* d_pos_in,
+                                  void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                  int32_t* d_pos_out, int64_t* d_out_offsets,
+                                  float* d_importance, float* d_pooled, int64_t out_capacity_rows,
+                                  void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------ kernel timing -----
  * Optional instrumentation for benchmarks: between slkv_profile_begin and slkv_profile_end
  * every kernel the library launches is bracketed by a HIP event pair on the call's stream.

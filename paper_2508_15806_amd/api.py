@@ -49,6 +49,34 @@ class LayerCall:
                               self.out_offsets, self.importance, self.pooled, stream)
 
 
+class RaggedCall:
+    """Device buffers + descriptor for repeated re-compression calls on one ragged cache shape."""
+
+    def __init__(self, dtype, B_, Hq, Hkv, d, w, in_offsets, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX,
+                 device="cuda", debug_scores=False, positions=True):
+        rows_in = int(in_offsets[-1])
+        self.rag = B.Ragged(B.SLKV_BF16 if dtype == "bf16" else B.SLKV_F32, B_, Hq, Hkv, d, w, in_offsets, budgets,
+                            pool_kernel, pool)
+        self.offsets, self.total_kept = B.slkv_recompress_sizes(self.rag)
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        rows = max(self.total_kept, 1)
+        self.k_out = torch.empty((rows, d), dtype=tdt, device=device)
+        self.v_out = torch.empty((rows, d), dtype=tdt, device=device)
+        self.kept_idx = torch.empty((rows,), dtype=torch.int32, device=device)
+        self.pos_out = torch.empty((rows,), dtype=torch.int32, device=device) if positions else None
+        self.out_offsets = torch.empty((B_ * Hkv + 1,), dtype=torch.int64, device=device)
+        self.workspace = torch.empty((B.slkv_recompress_workspace_bytes(self.rag),), dtype=torch.uint8, device=device)
+        self.importance = self.pooled = None
+        if debug_scores:
+            self.importance = torch.zeros((max(rows_in, 1),), dtype=torch.float32, device=device)
+            self.pooled = torch.zeros((max(rows_in, 1),), dtype=torch.float32, device=device)
+
+    def run(self, qwin, k_in, v_in, pos_in=None, stream=None):
+        B.slkv_recompress_layer(self.rag, qwin, k_in, v_in, self.k_out, self.v_out, self.kept_idx, self.workspace,
+                                pos_in, self.pos_out if pos_in is not None else None, self.out_offsets,
+                                self.importance, self.pooled, stream)
+
+
 def score_heads(rows, needle_start, needle_len, topk, acc=None, stream=None):
     """rows: [L,H,T,n] fp32 device tensor.  Returns (acc [L,H,5], scores [L,H,3]) float64 device tensors."""
     L, H, T, n = rows.shape

@@ -24,6 +24,7 @@ STATUS_NAMES = {0: "SLKV_OK", 1: "SLKV_ERR_NULL", 2: "SLKV_ERR_BAD_ARG", 3: "SLK
 EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads",
            "slkv_score_heads_workspace_bytes", "slkv_allocate_budgets", "slkv_fixed_from_beta",
            "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer",
+           "slkv_recompress_sizes", "slkv_recompress_workspace_bytes", "slkv_recompress_layer",
            "slkv_profile_begin", "slkv_profile_end"]
 
 KERNEL_NAMES = ["score_stats", "combine", "score_accum", "select", "gather", "row_cells", "head_reduce"]
@@ -46,6 +47,14 @@ class LayerDesc(C.Structure):
                 ("h_cu_seqlens", C.POINTER(C.c_int64)),
                 ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
                 ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+                ("h_budgets", C.POINTER(C.c_int32))]
+
+
+class RaggedDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32),
+                ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("w", C.c_int32),
+                ("pool_kernel", C.c_int32), ("pool", C.c_int32), ("reserved", C.c_int32),
+                ("h_in_offsets", C.POINTER(C.c_int64)),
                 ("h_budgets", C.POINTER(C.c_int32))]
 
 
@@ -76,6 +85,13 @@ def lib():
         L.slkv_compress_layer.restype = C.c_int
         L.slkv_compress_layer.argtypes = [C.POINTER(LayerDesc)] + [C.c_void_p] * 9 + [C.c_int64, C.c_void_p,
                                                                                       C.c_size_t, C.c_void_p]
+        L.slkv_recompress_sizes.restype = C.c_int
+        L.slkv_recompress_sizes.argtypes = [C.POINTER(RaggedDesc), C.c_void_p, C.c_void_p]
+        L.slkv_recompress_workspace_bytes.restype = C.c_int
+        L.slkv_recompress_workspace_bytes.argtypes = [C.POINTER(RaggedDesc), C.POINTER(C.c_size_t)]
+        L.slkv_recompress_layer.restype = C.c_int
+        L.slkv_recompress_layer.argtypes = [C.POINTER(RaggedDesc)] + [C.c_void_p] * 11 + [C.c_int64, C.c_void_p,
+                                                                                          C.c_size_t, C.c_void_p]
         L.slkv_score_heads_workspace_bytes.restype = C.c_size_t
         L.slkv_score_heads_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64]
         L.slkv_score_heads.restype = C.c_int
@@ -157,6 +173,41 @@ def slkv_compress_layer(layer, qwin, k, v, k_out, v_out, kept_idx, workspace, ou
                                      _ptr(kept_idx), _ptr(out_offsets), _ptr(importance), _ptr(pooled),
                                      int(k_out.shape[0]), _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                      _stream(stream)))
+
+
+class Ragged:
+    """Host-side descriptor of one re-compression call; keeps the numpy arrays it points to alive."""
+
+    def __init__(self, dtype, B, Hq, Hkv, d, w, in_offsets, budgets, pool_kernel=7, pool=SLKV_POOL_MAX):
+        self.offs = np.ascontiguousarray(in_offsets, dtype=np.int64)
+        self.budgets = np.ascontiguousarray(budgets, dtype=np.int32)
+        self.desc = RaggedDesc(C.sizeof(RaggedDesc), int(dtype), B, Hq, Hkv, d, w, pool_kernel, pool, 0,
+                               self.offs.ctypes.data_as(C.POINTER(C.c_int64)),
+                               self.budgets.ctypes.data_as(C.POINTER(C.c_int32)))
+        self.B, self.Hkv = B, Hkv
+
+
+def slkv_recompress_sizes(rag):
+    """Returns (out_offsets int64 [B*Hkv+1], total_kept)."""
+    offs = np.zeros(rag.B * rag.Hkv + 1, dtype=np.int64)
+    total = C.c_int64(0)
+    _check(lib().slkv_recompress_sizes(C.byref(rag.desc), offs.ctypes.data, C.addressof(total)))
+    return offs, int(total.value)
+
+
+def slkv_recompress_workspace_bytes(rag):
+    n = C.c_size_t(0)
+    _check(lib().slkv_recompress_workspace_bytes(C.byref(rag.desc), C.byref(n)))
+    return int(n.value)
+
+
+def slkv_recompress_layer(rag, qwin, k_in, v_in, k_out, v_out, kept_idx, workspace, pos_in=None, pos_out=None,
+                          out_offsets=None, importance=None, pooled=None, stream=None):
+    """Enqueues one re-compression of a ragged cache on `stream` (torch stream; default: current)."""
+    _check(lib().slkv_recompress_layer(C.byref(rag.desc), _ptr(qwin), _ptr(k_in), _ptr(v_in), _ptr(pos_in),
+                                       _ptr(k_out), _ptr(v_out), _ptr(kept_idx), _ptr(pos_out), _ptr(out_offsets),
+                                       _ptr(importance), _ptr(pooled), int(k_out.shape[0]), _ptr(workspace),
+                                       int(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
 def slkv_score_heads_workspace_bytes(L, H, T, n):

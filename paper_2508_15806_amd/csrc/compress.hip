@@ -397,6 +397,8 @@ struct GatherArgs {
   unsigned char* v_out;
   int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;   // elements
   int lanes_per_row, elt_bytes;
+  const int32_t* pos_in;   // optional: original position of every input row (ragged input)
+  int32_t* pos_out;        // optional: pos_in at the kept rows
 };
 
 constexpr int kSelThreads = 1024;
@@ -709,6 +711,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
       const int64_t o = ((row0 + row) * ga.lanes_per_row + c) * 16;
       *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
       *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
+      if (ga.pos_out && c == 0) ga.pos_out[row0 + row] = ga.pos_in[tok];
     }
   }
 }
@@ -731,46 +734,56 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable tab, const G
   const int64_t o = (row * ga.lanes_per_row + c) * 16;
   *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
   *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
+  if (ga.pos_out && c == 0) ga.pos_out[row] = ga.pos_in[tok];
 }
 
 // ------------------------------------------------------------------------------------------
 // Host side: planning, validation, launches.
+
+// One (sequence, KV head) segment as the kernels see it.
+struct Seg {
+  int64_t row_begin;   // first token row of the segment (multiplied by the token stride)
+  int64_t n;           // rows in the segment; the last w are the window
+  int64_t cap;         // capacity C of its head
+  int32_t head;        // multiplied by the head stride (0 for a ragged cache)
+  int64_t qrow_off;    // first row of the segment's [G*w][d] query block
+  int64_t score_off;   // offset of the segment in the importance / pooled arrays
+};
+
+// What both entry points reduce to: common shape parameters plus the list of segments.
+struct Geometry {
+  int dtype, Hq, Hkv, d, w, pool_kernel, pool;
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  int64_t score_elems;   // length of the importance / pooled arrays
+  std::vector<Seg> segs;
+};
+
 struct Plan {
   int R, Rpad, CH;
-  int64_t total_tokens;
   size_t part_bytes, lse_bytes, score_bytes;
   size_t off_part, off_lse, off_imp, off_pooled, total_bytes;
-  int groups;
 };
 
 static bool seg_ranked(int64_t n, int64_t w, int64_t cap) { return n > w && n > cap && cap > w; }
 
-static void make_plan(const slkv_layer_desc* d, Plan& p) {
-  p.R = (d->Hq / d->Hkv) * d->w;
+static void make_plan(const Geometry& g, Plan& p) {
+  p.R = (g.Hq / g.Hkv) * g.w;
   p.Rpad = (p.R + 31) / 32 * 32;
-  p.total_tokens = d->h_cu_seqlens[d->B] ;
   // keys to score over all ranked segments -> chunk length giving about 512 workgroups
   int64_t keys = 0;
-  for (int b = 0; b < d->B; ++b) {
-    const int64_t n = d->h_cu_seqlens[b + 1] - d->h_cu_seqlens[b];
-    for (int h = 0; h < d->Hkv; ++h)
-      if (seg_ranked(n, d->w, d->h_budgets[h])) keys += n - d->w;
-  }
+  for (const Seg& s : g.segs)
+    if (seg_ranked(s.n, g.w, s.cap)) keys += s.n - g.w;
   int64_t ch = (keys + 511) / 512;
   ch = (ch + 127) / 128 * 128;
   ch = std::max<int64_t>(256, std::min<int64_t>(ch, 1 << 16));
   p.CH = (int)ch;
   int64_t chunks = 0;
-  for (int b = 0; b < d->B; ++b) {
-    const int64_t n = d->h_cu_seqlens[b + 1] - d->h_cu_seqlens[b];
-    for (int h = 0; h < d->Hkv; ++h)
-      if (seg_ranked(n, d->w, d->h_budgets[h])) chunks += (n - d->w + ch - 1) / ch;
-  }
-  p.groups = (d->B * d->Hkv + kMaxSegPerLaunch - 1) / kMaxSegPerLaunch;
+  for (const Seg& s : g.segs)
+    if (seg_ranked(s.n, g.w, s.cap)) chunks += (s.n - g.w + ch - 1) / ch;
   auto align = [](size_t x) { return (x + 255) / 256 * 256; };
   p.part_bytes = align((size_t)std::max<int64_t>(chunks, 1) * p.Rpad * 2 * sizeof(float));
-  p.lse_bytes = align((size_t)d->B * d->Hkv * p.Rpad * sizeof(float));
-  p.score_bytes = align((size_t)std::max<int64_t>(1, (int64_t)d->Hkv * p.total_tokens) * sizeof(float));
+  p.lse_bytes = align(std::max<size_t>(g.segs.size(), 1) * p.Rpad * sizeof(float));
+  p.score_bytes = align((size_t)std::max<int64_t>(1, g.score_elems) * sizeof(float));
   p.off_part = 0;
   p.off_lse = p.off_part + p.part_bytes;
   p.off_imp = p.off_lse + p.lse_bytes;
@@ -778,43 +791,86 @@ static void make_plan(const slkv_layer_desc* d, Plan& p) {
   p.total_bytes = p.off_pooled + p.score_bytes;
 }
 
+static void layer_geometry(const slkv_layer_desc* d, Geometry& g) {
+  g.dtype = d->dtype; g.Hq = d->Hq; g.Hkv = d->Hkv; g.d = d->d; g.w = d->w;
+  g.pool_kernel = d->pool_kernel; g.pool = d->pool;
+  g.k_stride_tok = d->k_stride_tok; g.k_stride_head = d->k_stride_head;
+  g.v_stride_tok = d->v_stride_tok; g.v_stride_head = d->v_stride_head;
+  g.score_elems = (int64_t)d->Hkv * d->h_cu_seqlens[d->B];
+  const int G = d->Hq / d->Hkv;
+  g.segs.resize((size_t)d->B * d->Hkv);
+  for (int b = 0; b < d->B; ++b) {
+    const int64_t n = d->h_cu_seqlens[b + 1] - d->h_cu_seqlens[b];
+    for (int h = 0; h < d->Hkv; ++h) {
+      Seg& s = g.segs[(size_t)b * d->Hkv + h];
+      s.row_begin = d->h_cu_seqlens[b];
+      s.n = n;
+      s.cap = d->h_budgets[h];
+      s.head = h;
+      s.qrow_off = ((int64_t)b * d->Hq + (int64_t)h * G) * d->w;
+      s.score_off = (int64_t)d->Hkv * d->h_cu_seqlens[b] + (int64_t)h * n;
+    }
+  }
+}
+
+static void ragged_geometry(const slkv_ragged_desc* d, Geometry& g) {
+  g.dtype = d->dtype; g.Hq = d->Hq; g.Hkv = d->Hkv; g.d = d->d; g.w = d->w;
+  g.pool_kernel = d->pool_kernel; g.pool = d->pool;
+  g.k_stride_tok = g.v_stride_tok = d->d;     // packed rows
+  g.k_stride_head = g.v_stride_head = 0;      // a segment's rows are addressed by row_begin alone
+  const int S = d->B * d->Hkv;
+  g.score_elems = d->h_in_offsets[S] - d->h_in_offsets[0];
+  const int G = d->Hq / d->Hkv;
+  g.segs.resize((size_t)S);
+  for (int i = 0; i < S; ++i) {
+    const int b = i / d->Hkv, h = i % d->Hkv;
+    Seg& s = g.segs[(size_t)i];
+    s.row_begin = d->h_in_offsets[i];
+    s.n = d->h_in_offsets[i + 1] - d->h_in_offsets[i];
+    s.cap = d->h_budgets[h];
+    s.head = 0;
+    s.qrow_off = ((int64_t)b * d->Hq + (int64_t)h * G) * d->w;
+    s.score_off = d->h_in_offsets[i] - d->h_in_offsets[0];
+  }
+}
+
 template <int DK, int MT, int RB>
 static void launch_bf16(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
-                        const slkv_layer_desc* d, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+                        const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
   if (pass == 1)
     hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 1>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
-                       (const uint16_t*)k, d->k_stride_tok, d->k_stride_head, p.R, p.Rpad, d->w, p.CH, c_log2, part, lse, imp);
+                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp);
   else
     hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 2>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
-                       (const uint16_t*)k, d->k_stride_tok, d->k_stride_head, p.R, p.Rpad, d->w, p.CH, c_log2, part, lse, imp);
+                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp);
 }
 
 template <int DK>
 static void launch_bf16_rows(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
-                             const slkv_layer_desc* d, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
-  if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
-  else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
-  else if (p.R <= 256) launch_bf16<DK, 2, 4>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
-  else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+                             const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+  if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
+  else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
+  else if (p.R <= 256) launch_bf16<DK, 2, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
+  else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
 }
 
 static void launch_score(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
-                         const slkv_layer_desc* d, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
-  if (d->dtype == SLKV_BF16) {
-    if (d->d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
-    else launch_bf16_rows<64>(pass, grid, st, tab, q, k, d, p, c_log2, part, lse, imp);
+                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+  if (g.dtype == SLKV_BF16) {
+    if (g.d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
+    else launch_bf16_rows<64>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
   hipLaunchKernelGGL((score_f32_kernel<DKV, PS>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
-                     d->k_stride_tok, d->k_stride_head, p.R, p.Rpad, d->w, p.CH, c_log2, part, lse, imp)
-    if (d->d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
+                     g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp)
+    if (g.d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
     else { if (pass == 1) SLKV_F32_LAUNCH(64, 1); else SLKV_F32_LAUNCH(64, 2); }
 #undef SLKV_F32_LAUNCH
   }
 }
 
 template <int RADIUS>
-static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, const slkv_layer_desc* d,
+static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, const Geometry& g,
                                   bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
                                   int64_t* d_out_offsets, int is_last, const GatherArgs& ga) {
   static bool attr_set = false;   // LDS above 64 KB per workgroup has to be requested once per kernel
@@ -825,67 +881,52 @@ static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, c
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((select_kernel<RADIUS>), dim3(ns), dim3(kSelThreads), lds, st, tab, d->w, d->pool_kernel, d->pool,
+  hipLaunchKernelGGL((select_kernel<RADIUS>), dim3(ns), dim3(kSelThreads), lds, st, tab, g.w, g.pool_kernel, g.pool,
                      (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
   return hipSuccess;
 }
 
-static hipError_t launch_select(int ns, hipStream_t st, const SegTable& tab, const slkv_layer_desc* d, bool write_pooled,
+static hipError_t launch_select(int ns, hipStream_t st, const SegTable& tab, const Geometry& g, bool write_pooled,
                                 const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets, int is_last,
                                 const GatherArgs& ga) {
-  const int radius = d->pool == SLKV_POOL_NONE ? 0 : d->pool_kernel / 2;
+  const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
   switch (radius) {
-    case 0: return launch_select_r<0>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    case 1: return launch_select_r<1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    case 2: return launch_select_r<2>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    case 3: return launch_select_r<3>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    default: return launch_select_r<-1>(ns, st, tab, d, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 0: return launch_select_r<0>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 1: return launch_select_r<1>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 2: return launch_select_r<2>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 3: return launch_select_r<3>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    default: return launch_select_r<-1>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
   }
 }
 
-}  // namespace slkv
-
-using namespace slkv;
-
-extern "C" slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes) {
-  clear_error();
-  if (!bytes) return fail(SLKV_ERR_NULL, "bytes is NULL");
-  slkv_status st = validate_desc(desc);
-  if (st != SLKV_OK) return st;
-  Plan p;
-  make_plan(desc, p);
-  *bytes = p.total_bytes;
-  return SLKV_OK;
-}
-
-extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin, const void* d_k,
-                                           const void* d_v, void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
-                                           int64_t* d_out_offsets, float* d_importance, float* d_pooled,
-                                           int64_t out_capacity_rows, void* d_workspace, size_t workspace_bytes,
-                                           void* hip_stream) {
-  clear_error();
-  slkv_status vs = validate_desc(desc);
-  if (vs != SLKV_OK) return vs;
+// Checks and launches shared by the two entry points.
+static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const void* d_k, const void* d_v,
+                                const int32_t* d_pos_in, void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                int32_t* d_pos_out, int64_t* d_out_offsets, float* d_importance, float* d_pooled,
+                                int64_t out_capacity_rows, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   if (!d_qwin || !d_k || !d_v || !d_k_out || !d_v_out || !d_kept_idx || !d_workspace)
     return fail(SLKV_ERR_NULL, "a required device pointer is NULL");
-  const void* ptrs[] = {d_qwin, d_k, d_v, d_k_out, d_v_out, d_kept_idx, d_out_offsets, d_importance, d_pooled, d_workspace};
+  if ((d_pos_in == nullptr) != (d_pos_out == nullptr))
+    return fail(SLKV_ERR_NULL, "d_pos_in and d_pos_out must be given together");
+  const void* ptrs[] = {d_qwin, d_k, d_v, d_pos_in, d_k_out, d_v_out, d_kept_idx, d_pos_out, d_out_offsets,
+                        d_importance, d_pooled, d_workspace};
   for (const void* ptr : ptrs)
     if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(SLKV_ERR_BAD_ARG, "device pointer %p not 16-byte aligned", ptr);
-  if ((int64_t)desc->B * desc->Hq * desc->w >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "B*Hq*w >= 2^31");
-  for (int b = 0; b < desc->B; ++b) {   // the kernels address a sequence's keys with 32-bit byte offsets
-    const int64_t n = desc->h_cu_seqlens[b + 1] - desc->h_cu_seqlens[b];
-    if (n * desc->k_stride_tok * (desc->dtype == SLKV_BF16 ? 2 : 4) >= (int64_t(1) << 31))
-      return fail(SLKV_ERR_UNSUPPORTED, "sequence %d spans 2 GiB or more of K", b);
+  const int elt = g.dtype == SLKV_BF16 ? 2 : 4;
+  const int64_t S = (int64_t)g.segs.size();
+  if (S / g.Hkv * g.Hq * g.w >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "B*Hq*w >= 2^31");
+  int64_t total_kept = 0;
+  for (int64_t i = 0; i < S; ++i) {   // the kernels address a segment's keys with 32-bit byte offsets
+    const Seg& s = g.segs[(size_t)i];
+    if (s.n * g.k_stride_tok * elt >= (int64_t(1) << 31))
+      return fail(SLKV_ERR_UNSUPPORTED, "segment %lld spans 2 GiB or more of K", (long long)i);
+    total_kept += kept_rows(s.n, g.w, s.cap);
   }
+  if (total_kept >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "kept rows >= 2^31");
   Plan p;
-  make_plan(desc, p);
+  make_plan(g, p);
   if (workspace_bytes < p.total_bytes)
     return fail(SLKV_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, p.total_bytes);
-  int64_t total_kept = 0;
-  for (int b = 0; b < desc->B; ++b) {
-    const int64_t n = desc->h_cu_seqlens[b + 1] - desc->h_cu_seqlens[b];
-    for (int h = 0; h < desc->Hkv; ++h) total_kept += kept_rows(n, desc->w, desc->h_budgets[h]);
-  }
   if (out_capacity_rows < total_kept)
     return fail(SLKV_ERR_CAPACITY, "out_capacity_rows %lld < %lld", (long long)out_capacity_rows, (long long)total_kept);
 
@@ -895,47 +936,44 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
   float* lse = (float*)(ws + p.off_lse);
   float* imp = d_importance ? d_importance : (float*)(ws + p.off_imp);
   float* pooled = d_pooled ? d_pooled : (float*)(ws + p.off_pooled);
-  const int G = desc->Hq / desc->Hkv;
-  const float c_log2 = (float)(1.4426950408889634 / std::sqrt((double)desc->d));
-  const int elt = desc->dtype == SLKV_BF16 ? 2 : 4;
-  const int lanes_per_row = desc->d * elt / 16;
+  const float c_log2 = (float)(1.4426950408889634 / std::sqrt((double)g.d));
+  const int lanes_per_row = g.d * elt / 16;
 
   GatherArgs ga;
   ga.k = (const unsigned char*)d_k;
   ga.v = (const unsigned char*)d_v;
   ga.k_out = (unsigned char*)d_k_out;
   ga.v_out = (unsigned char*)d_v_out;
-  ga.k_stride_tok = desc->k_stride_tok;
-  ga.k_stride_head = desc->k_stride_head;
-  ga.v_stride_tok = desc->v_stride_tok;
-  ga.v_stride_head = desc->v_stride_head;
+  ga.k_stride_tok = g.k_stride_tok;
+  ga.k_stride_head = g.k_stride_head;
+  ga.v_stride_tok = g.v_stride_tok;
+  ga.v_stride_head = g.v_stride_head;
   ga.lanes_per_row = lanes_per_row;
   ga.elt_bytes = elt;
+  ga.pos_in = d_pos_in;
+  ga.pos_out = d_pos_out;
 
-  const int S = desc->B * desc->Hkv;
   int64_t out_run = 0;
-  for (int s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
+  for (int64_t s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
     SegTable tab;
     std::memset(&tab, 0, sizeof(tab));
-    const int ns = std::min(kMaxSegPerLaunch, S - s0);
+    const int ns = (int)std::min<int64_t>(kMaxSegPerLaunch, S - s0);
     tab.nseg = ns;
     int chunks = 0;
     for (int i = 0; i < ns; ++i) {
-      const int s = s0 + i, b = s / desc->Hkv, h = s % desc->Hkv;
-      const int64_t n = desc->h_cu_seqlens[b + 1] - desc->h_cu_seqlens[b];
-      const int64_t cap = desc->h_budgets[h];
-      tab.tok_begin[i] = (int32_t)desc->h_cu_seqlens[b];
-      tab.n[i] = (int32_t)n;
-      const bool all = n <= desc->w || n <= cap;
-      tab.kkeep[i] = all ? -1 : (int32_t)std::min<int64_t>(std::max<int64_t>(cap - desc->w, 0), n - desc->w);
+      const Seg& sg = g.segs[(size_t)(s0 + i)];
+      tab.tok_begin[i] = (int32_t)sg.row_begin;
+      tab.n[i] = (int32_t)sg.n;
+      const bool all = sg.n <= g.w || sg.n <= sg.cap;
+      tab.kkeep[i] = all ? -1 : (int32_t)std::min<int64_t>(std::max<int64_t>(sg.cap - g.w, 0), sg.n - g.w);
       tab.out_off[i] = (int32_t)out_run;
-      out_run += kept_rows(n, desc->w, cap);
-      tab.head[i] = h;
-      tab.qrow_off[i] = (int32_t)(((int64_t)b * desc->Hq + (int64_t)h * G) * desc->w);
-      tab.score_off[i] = (int32_t)((int64_t)desc->Hkv * desc->h_cu_seqlens[b] + (int64_t)h * n);
+      out_run += kept_rows(sg.n, g.w, sg.cap);
+      tab.head[i] = sg.head;
+      tab.qrow_off[i] = (int32_t)sg.qrow_off;
+      tab.score_off[i] = (int32_t)sg.score_off;
       tab.chunk_begin[i] = chunks;
-      tab.seg_global[i] = s;
-      if (seg_ranked(n, desc->w, cap)) chunks += (int)((n - desc->w + p.CH - 1) / p.CH);
+      tab.seg_global[i] = (int32_t)(s0 + i);
+      if (seg_ranked(sg.n, g.w, sg.cap)) chunks += (int)((sg.n - g.w + p.CH - 1) / p.CH);
     }
     tab.out_off[ns] = (int32_t)out_run;
     tab.chunk_begin[ns] = chunks;
@@ -948,7 +986,7 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
     if (chunks > 0) {
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_STATS, st);
-        launch_score(1, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+        launch_score(1, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp);
       }
       {
         ScopedKernelTimer tm(SLKV_K_COMBINE, st);
@@ -956,12 +994,12 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
       }
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_ACCUM, st);
-        launch_score(2, chunks, st, tab, d_qwin, d_k, desc, p, c_log2, part, lse, imp);
+        launch_score(2, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp);
       }
     }
     {
       ScopedKernelTimer tm(SLKV_K_SELECT, st);
-      hipError_t se = launch_select(ns, st, tab, desc, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets,
+      hipError_t se = launch_select(ns, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets,
                                     (int)(s0 + ns == S), ga);
       if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
     }
@@ -977,4 +1015,62 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
     if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
   }
   return SLKV_OK;
+}
+
+}  // namespace slkv
+
+using namespace slkv;
+
+extern "C" slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes) {
+  clear_error();
+  if (!bytes) return fail(SLKV_ERR_NULL, "bytes is NULL");
+  slkv_status st = validate_desc(desc);
+  if (st != SLKV_OK) return st;
+  Geometry g;
+  layer_geometry(desc, g);
+  Plan p;
+  make_plan(g, p);
+  *bytes = p.total_bytes;
+  return SLKV_OK;
+}
+
+extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin, const void* d_k,
+                                           const void* d_v, void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                           int64_t* d_out_offsets, float* d_importance, float* d_pooled,
+                                           int64_t out_capacity_rows, void* d_workspace, size_t workspace_bytes,
+                                           void* hip_stream) {
+  clear_error();
+  slkv_status vs = validate_desc(desc);
+  if (vs != SLKV_OK) return vs;
+  Geometry g;
+  layer_geometry(desc, g);
+  return run_geometry(g, d_qwin, d_k, d_v, nullptr, d_k_out, d_v_out, d_kept_idx, nullptr, d_out_offsets, d_importance,
+                      d_pooled, out_capacity_rows, d_workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" slkv_status slkv_recompress_workspace_bytes(const slkv_ragged_desc* desc, size_t* bytes) {
+  clear_error();
+  if (!bytes) return fail(SLKV_ERR_NULL, "bytes is NULL");
+  slkv_status st = validate_ragged_desc(desc);
+  if (st != SLKV_OK) return st;
+  Geometry g;
+  ragged_geometry(desc, g);
+  Plan p;
+  make_plan(g, p);
+  *bytes = p.total_bytes;
+  return SLKV_OK;
+}
+
+extern "C" slkv_status slkv_recompress_layer(const slkv_ragged_desc* desc, const void* d_qwin, const void* d_k_in,
+                                             const void* d_v_in, const int32_t* d_pos_in, void* d_k_out, void* d_v_out,
+                                             int32_t* d_kept_idx, int32_t* d_pos_out, int64_t* d_out_offsets,
+                                             float* d_importance, float* d_pooled, int64_t out_capacity_rows,
+                                             void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  slkv_status vs = validate_ragged_desc(desc);
+  if (vs != SLKV_OK) return vs;
+  Geometry g;
+  ragged_geometry(desc, g);
+  return run_geometry(g, d_qwin, d_k_in, d_v_in, d_pos_in, d_k_out, d_v_out, d_kept_idx, d_pos_out,
+                      d_out_offsets, d_importance, d_pooled, out_capacity_rows, d_workspace, workspace_bytes, hip_stream);
 }

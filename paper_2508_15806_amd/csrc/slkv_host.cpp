@@ -32,32 +32,39 @@ int64_t kept_rows(int64_t n, int64_t w, int64_t cap) {
   return std::max<int64_t>(cap, w);
 }
 
+// Checks of the shape parameters the two descriptors share.
+static slkv_status validate_shape(int32_t dtype, int32_t B, int32_t Hq, int32_t Hkv, int32_t dd, int32_t w,
+                                  int32_t pool_kernel, int32_t pool, int32_t reserved, const int32_t* h_budgets) {
+  if (dtype != SLKV_F32 && dtype != SLKV_BF16) return fail(SLKV_ERR_BAD_ARG, "unknown dtype %d", dtype);
+  if (B < 1 || Hq < 1 || Hkv < 1 || w < 1) return fail(SLKV_ERR_BAD_ARG, "B, Hq, Hkv, w must be >= 1");
+  if (B > (1 << 20) || Hkv > (1 << 16) || Hq > (1 << 16)) return fail(SLKV_ERR_BAD_ARG, "B, Hq or Hkv too large");
+  if (Hq % Hkv) return fail(SLKV_ERR_BAD_ARG, "Hq %% Hkv != 0");
+  if (dd != 64 && dd != 128) return fail(SLKV_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", dd);
+  int64_t rows = (int64_t)(Hq / Hkv) * w;
+  if (rows > kMaxRows) return fail(SLKV_ERR_UNSUPPORTED, "(Hq/Hkv)*w = %lld rows > %d", (long long)rows, kMaxRows);
+  if (pool != SLKV_POOL_NONE && pool != SLKV_POOL_MAX && pool != SLKV_POOL_AVG)
+    return fail(SLKV_ERR_BAD_ARG, "unknown pool mode %d", pool);
+  if (pool_kernel < 1 || pool_kernel > kMaxPool || pool_kernel % 2 == 0)
+    return fail(SLKV_ERR_BAD_ARG, "pool_kernel %d must be odd and in 1..%d", pool_kernel, kMaxPool);
+  if (reserved != 0) return fail(SLKV_ERR_BAD_ARG, "desc.reserved must be 0");
+  if (!h_budgets) return fail(SLKV_ERR_NULL, "h_budgets is NULL");
+  for (int h = 0; h < Hkv; ++h)
+    if (h_budgets[h] < 0) return fail(SLKV_ERR_BAD_ARG, "budget[%d] < 0", h);
+  return SLKV_OK;
+}
+
 slkv_status validate_desc(const slkv_layer_desc* d) {
   if (!d) return fail(SLKV_ERR_NULL, "desc is NULL");
   if (d->struct_size != sizeof(slkv_layer_desc))
     return fail(SLKV_ERR_BAD_ARG, "desc.struct_size %u != %zu", d->struct_size, sizeof(slkv_layer_desc));
-  if (d->dtype != SLKV_F32 && d->dtype != SLKV_BF16) return fail(SLKV_ERR_BAD_ARG, "unknown dtype %d", d->dtype);
-  if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->w < 1)
-    return fail(SLKV_ERR_BAD_ARG, "B, Hq, Hkv, w must be >= 1");
-  if (d->B > (1 << 20) || d->Hkv > (1 << 16) || d->Hq > (1 << 16))
-    return fail(SLKV_ERR_BAD_ARG, "B, Hq or Hkv too large");
-  if (d->Hq % d->Hkv) return fail(SLKV_ERR_BAD_ARG, "Hq %% Hkv != 0");
-  if (d->d != 64 && d->d != 128) return fail(SLKV_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", d->d);
-  int64_t rows = (int64_t)(d->Hq / d->Hkv) * d->w;
-  if (rows > kMaxRows) return fail(SLKV_ERR_UNSUPPORTED, "(Hq/Hkv)*w = %lld rows > %d", (long long)rows, kMaxRows);
-  if (d->pool != SLKV_POOL_NONE && d->pool != SLKV_POOL_MAX && d->pool != SLKV_POOL_AVG)
-    return fail(SLKV_ERR_BAD_ARG, "unknown pool mode %d", d->pool);
-  if (d->pool_kernel < 1 || d->pool_kernel > kMaxPool || d->pool_kernel % 2 == 0)
-    return fail(SLKV_ERR_BAD_ARG, "pool_kernel %d must be odd and in 1..%d", d->pool_kernel, kMaxPool);
-  if (d->reserved != 0) return fail(SLKV_ERR_BAD_ARG, "desc.reserved must be 0");
+  slkv_status st = validate_shape(d->dtype, d->B, d->Hq, d->Hkv, d->d, d->w, d->pool_kernel, d->pool, d->reserved,
+                                  d->h_budgets);
+  if (st != SLKV_OK) return st;
   if (!d->h_cu_seqlens) return fail(SLKV_ERR_NULL, "h_cu_seqlens is NULL");
-  if (!d->h_budgets) return fail(SLKV_ERR_NULL, "h_budgets is NULL");
   if (d->h_cu_seqlens[0] < 0) return fail(SLKV_ERR_BAD_ARG, "cu_seqlens[0] < 0");
   for (int b = 0; b < d->B; ++b)
     if (d->h_cu_seqlens[b + 1] < d->h_cu_seqlens[b]) return fail(SLKV_ERR_BAD_ARG, "cu_seqlens not monotone at %d", b);
   if (d->h_cu_seqlens[d->B] >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "cu_seqlens[B] >= 2^31");
-  for (int h = 0; h < d->Hkv; ++h)
-    if (d->h_budgets[h] < 0) return fail(SLKV_ERR_BAD_ARG, "budget[%d] < 0", h);
   const int64_t strides[4] = {d->k_stride_tok, d->k_stride_head, d->v_stride_tok, d->v_stride_head};
   const int64_t align_elems = d->dtype == SLKV_BF16 ? 8 : 4;
   for (int i = 0; i < 4; ++i) {
@@ -66,6 +73,22 @@ slkv_status validate_desc(const slkv_layer_desc* d) {
   if (d->k_stride_tok < d->d || d->v_stride_tok < d->d) return fail(SLKV_ERR_BAD_ARG, "token stride < head_dim");
   int64_t total = (int64_t)d->Hkv * d->h_cu_seqlens[d->B];
   if (total >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "Hkv * tokens >= 2^31");
+  return SLKV_OK;
+}
+
+slkv_status validate_ragged_desc(const slkv_ragged_desc* d) {
+  if (!d) return fail(SLKV_ERR_NULL, "desc is NULL");
+  if (d->struct_size != sizeof(slkv_ragged_desc))
+    return fail(SLKV_ERR_BAD_ARG, "desc.struct_size %u != %zu", d->struct_size, sizeof(slkv_ragged_desc));
+  slkv_status st = validate_shape(d->dtype, d->B, d->Hq, d->Hkv, d->d, d->w, d->pool_kernel, d->pool, d->reserved,
+                                  d->h_budgets);
+  if (st != SLKV_OK) return st;
+  if (!d->h_in_offsets) return fail(SLKV_ERR_NULL, "h_in_offsets is NULL");
+  if (d->h_in_offsets[0] < 0) return fail(SLKV_ERR_BAD_ARG, "in_offsets[0] < 0");
+  const int64_t S = (int64_t)d->B * d->Hkv;
+  for (int64_t s = 0; s < S; ++s)
+    if (d->h_in_offsets[s + 1] < d->h_in_offsets[s]) return fail(SLKV_ERR_BAD_ARG, "in_offsets not monotone at %lld", (long long)s);
+  if (d->h_in_offsets[S] >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "in_offsets[B*Hkv] >= 2^31");
   return SLKV_OK;
 }
 
@@ -227,6 +250,21 @@ extern "C" slkv_status slkv_compacted_sizes(const slkv_layer_desc* desc, int64_t
     }
   }
   if (h_out_offsets) h_out_offsets[(size_t)desc->B * desc->Hkv] = run;
+  if (total_kept) *total_kept = run;
+  return SLKV_OK;
+}
+
+slkv_status slkv_recompress_sizes(const slkv_ragged_desc* desc, int64_t* h_out_offsets, int64_t* total_kept) {
+  clear_error();
+  slkv_status st = validate_ragged_desc(desc);
+  if (st != SLKV_OK) return st;
+  int64_t run = 0;
+  const int64_t S = (int64_t)desc->B * desc->Hkv;
+  for (int64_t s = 0; s < S; ++s) {
+    if (h_out_offsets) h_out_offsets[s] = run;
+    run += kept_rows(desc->h_in_offsets[s + 1] - desc->h_in_offsets[s], desc->w, desc->h_budgets[s % desc->Hkv]);
+  }
+  if (h_out_offsets) h_out_offsets[S] = run;
   if (total_kept) *total_kept = run;
   return SLKV_OK;
 }

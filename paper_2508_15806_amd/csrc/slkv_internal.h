@@ -21,6 +21,7 @@ int64_t kept_rows(int64_t n, int64_t w, int64_t cap);
 
 // Checks everything in the descriptor that can be checked on the host.
 slkv_status validate_desc(const slkv_layer_desc* d);
+slkv_status validate_ragged_desc(const slkv_ragged_desc* d);
 
 // Records a HIP event pair around one kernel launch while profiling is on (see
 // slkv_profile_begin); does nothing otherwise.

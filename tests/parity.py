@@ -80,3 +80,71 @@ def compare_layer(lay, budgets, gpu, pool_kernel=7, pool=B.SLKV_POOL_MAX, ref=No
             rep["tolerant"] += 1
             rep["diffs"].append((s, sorted(gset ^ set(want[:kk].tolist()))))
     return rep
+
+
+def run_gpu_ragged(rc, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX, positions=True):
+    import torch
+    call = api.RaggedCall(rc.dtype, rc.B, rc.Hq, rc.Hkv, rc.d, rc.w, rc.in_offsets, budgets, pool_kernel, pool,
+                          debug_scores=True, positions=positions)
+    q = api.to_device(rc.qwin, rc.dtype)
+    k = api.to_device(rc.k_rows, rc.dtype)
+    v = api.to_device(rc.v_rows, rc.dtype)
+    pos = torch.from_numpy(rc.pos_in).cuda() if positions else None
+    call.run(q, k, v, pos)
+    torch.cuda.synchronize()
+    return dict(call=call, offsets=call.out_offsets.cpu().numpy(), kept=call.kept_idx.cpu().numpy(),
+                k_out=api.to_host(call.k_out), v_out=api.to_host(call.v_out),
+                pos_out=call.pos_out.cpu().numpy() if positions else None,
+                importance=call.importance.cpu().numpy(), pooled=call.pooled.cpu().numpy())
+
+
+def compare_ragged(rc, budgets, gpu, pool_kernel=7, pool=B.SLKV_POOL_MAX):
+    """As compare_layer, for slkv_recompress_layer against oracle.recompress_layer."""
+    eps = TOL[rc.dtype]
+    ref = oracle.recompress_layer(rc.qwin, rc.k_rows, rc.v_rows, rc.in_offsets, budgets, rc.w, pool_kernel, pool,
+                                  pos_in=rc.pos_in)
+    host_offs, total = B.slkv_recompress_sizes(gpu["call"].rag)
+    assert np.array_equal(ref["out_offsets"], host_offs), "host offsets differ from the oracle"
+    assert np.array_equal(ref["out_offsets"], gpu["offsets"]), "device offsets differ from the oracle"
+    G = rc.Hq // rc.Hkv
+    rep = dict(segments=0, ranked=0, exact=0, tolerant=0, max_rel=0.0)
+    for s in range(rc.B * rc.Hkv):
+        r0, r1 = int(rc.in_offsets[s]), int(rc.in_offsets[s + 1])
+        n = r1 - r0
+        seg = ref["segments"][s]
+        o0, o1 = int(ref["out_offsets"][s]), int(ref["out_offsets"][s + 1])
+        got = gpu["kept"][o0:o1].astype(np.int64)
+        rep["segments"] += 1
+        assert got.min(initial=0) >= 0 and got.max(initial=0) < max(n, 1)
+        assert np.array_equal(gpu["k_out"][o0:o1], rc.k_rows[r0 + got]), "K gather mismatch seg %d" % s
+        assert np.array_equal(gpu["v_out"][o0:o1], rc.v_rows[r0 + got]), "V gather mismatch seg %d" % s
+        if gpu["pos_out"] is not None:
+            assert np.array_equal(gpu["pos_out"][o0:o1], rc.pos_in[r0 + got]), "positions mismatch seg %d" % s
+        want = seg["kept_idx"]
+        if seg["pooled"] is None or seg["k"] == 0:
+            assert np.array_equal(got, want), "unranked segment %d differs" % s
+            rep["exact"] += 1
+            continue
+        rep["ranked"] += 1
+        m, kk = n - rc.w, seg["k"]
+        so = r0 - int(rc.in_offsets[0])
+        for name, refv in (("importance", seg["importance"]), ("pooled", seg["pooled"])):
+            g = gpu[name][so:so + m].astype(np.float64)
+            floor = rc.w * G / m * 1e-3
+            rel = np.abs(g - refv) / np.maximum(np.abs(refv), floor)
+            rep["max_rel"] = max(rep["max_rel"], float(rel.max()))
+            assert rel.max() <= eps, "%s of segment %d off by %.3g (tolerance %.3g)" % (name, s, rel.max(), eps)
+        assert np.array_equal(got[kk:], want[kk:]), "window of segment %d differs" % s
+        assert (np.diff(got[:kk]) > 0).all(), "history of segment %d not ascending" % s
+        if np.array_equal(got, want):
+            rep["exact"] += 1
+            continue
+        tau, pooled = seg["tau"], seg["pooled"]
+        sure_in = set(np.nonzero(pooled > tau * (1 + eps))[0].tolist())
+        sure_out = set(np.nonzero(pooled < tau * (1 - eps))[0].tolist())
+        gset = set(got[:kk].tolist())
+        assert len(gset) == kk
+        assert sure_in <= gset, "segment %d misses a clearly-in position" % s
+        assert not (gset & sure_out), "segment %d holds a clearly-out position" % s
+        rep["tolerant"] += 1
+    return rep

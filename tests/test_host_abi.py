@@ -153,3 +153,56 @@ def test_score_heads_validation():
     assert call(a11=C.c_size_t(8)) == 5
     assert call(a0=C.c_void_p(4100)) == 2
     assert B.slkv_score_heads_workspace_bytes(2, 2, 2, 64) == 2 * 2 * 2 * 4 * 8
+
+
+def make_ragged(**over):
+    p = dict(dtype=B.SLKV_BF16, B=2, Hq=4, Hkv=2, d=128, w=16, in_offsets=[0, 100, 130, 130, 190], budgets=[40, 120],
+             pool_kernel=7, pool=B.SLKV_POOL_MAX)
+    p.update(over)
+    return B.Ragged(p["dtype"], p["B"], p["Hq"], p["Hkv"], p["d"], p["w"], p["in_offsets"], p["budgets"],
+                    p["pool_kernel"], p["pool"])
+
+
+def test_recompress_sizes_follow_algorithm3():
+    rag = make_ragged()
+    offs, total = B.slkv_recompress_sizes(rag)
+    # lengths 100, 30, 0, 60 with capacities 40, 120, 40, 120: 40 kept, all 30, nothing, all 60
+    assert offs.tolist() == [0, 40, 70, 70, 130] and total == 130
+    lens = [5, 17, 300, 64, 16, 1000]
+    caps = [3, 100]
+    rag = make_ragged(B=3, in_offsets=np.concatenate([[0], np.cumsum(lens)]), budgets=caps)
+    offs, total = B.slkv_recompress_sizes(rag)
+    want = [oracle.kept_count(n, 16, caps[i % 2]) for i, n in enumerate(lens)]
+    assert np.diff(offs).tolist() == want and total == sum(want)
+    assert B.slkv_recompress_workspace_bytes(rag) > 0
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(d=96), 4), (dict(w=0), 2), (dict(pool_kernel=4), 2), (dict(Hq=7), 2), (dict(budgets=[-1, 5]), 2),
+    (dict(in_offsets=[0, 100, 90, 130, 190]), 2), (dict(in_offsets=[-1, 100, 130, 130, 190]), 2),
+    (dict(in_offsets=[0, 100, 130, 130, 2 ** 31]), 2), (dict(dtype=7), 2),
+])
+def test_ragged_descriptor_validation(over, status):
+    rag = make_ragged(**over)
+    with pytest.raises(B.SlkvError) as e:
+        B.slkv_recompress_sizes(rag)
+    assert e.value.status == status
+
+
+def test_recompress_rejects_before_touching_the_gpu():
+    rag = make_ragged()
+    L = B.lib()
+    null, fake, odd = C.c_void_p(0), C.c_void_p(4096), C.c_void_p(4100)
+    big = C.c_size_t(1 << 40)
+
+    def call(q, kin, vin, pin, ko, vo, idx, po, cap, ws, wsb):
+        return L.slkv_recompress_layer(C.byref(rag.desc), q, kin, vin, pin, ko, vo, idx, po, null, null, null,
+                                       C.c_int64(cap), ws, wsb, null)
+    assert call(null, null, null, null, null, null, null, null, 10, null, C.c_size_t(0)) == 1   # NULL pointers
+    assert call(fake, fake, fake, fake, fake, fake, fake, null, 1000, fake, big) == 1           # pos_in without pos_out
+    assert call(fake, fake, fake, null, fake, fake, fake, null, 1000, fake, C.c_size_t(0)) == 5  # workspace too small
+    assert call(fake, fake, fake, null, fake, fake, fake, null, 10, fake, big) == 6             # output capacity
+    assert call(odd, fake, fake, null, fake, fake, fake, null, 1000, fake, big) == 2            # misaligned pointer
+    bad = B.RaggedDesc()
+    assert L.slkv_recompress_layer(C.byref(bad), fake, fake, fake, null, fake, fake, fake, null, null, null, null,
+                                   C.c_int64(1000), fake, big, null) == 2                       # struct_size
