@@ -23,8 +23,8 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/compress_layer_c3_avg256_rocprofv3.md): scoring pass 1, 63776 KiB read + 947 KiB written.
-MEASURED_TRAFFIC_BYTES = 66.3e6
+# (profiles/compress_layer_c3_avg256_rocprofv3.md): scoring pass 1, 67564 KiB read + 1000 KiB written.
+MEASURED_TRAFFIC_BYTES = 70.2e6
 
 
 def parse():
@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--avg", type=int, default=256, help="average budget per KV head (64, 256 or 1024)")
     ap.add_argument("--no-stage1", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-recompress", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the other budgets of the sweep")
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -189,7 +191,7 @@ def main():
     # other budgets of the sweep (same inputs, shorter loops)
     sweep = {}
     for avg in wl.C3_BUDGETS:
-        if avg == args.avg:
+        if avg == args.avg or args.no_sweep:
             continue
         bud = B.slkv_allocate_budgets(inf, Hkv, avg, 16)
         cs = [api.LayerCall("bf16", 1, Hq, Hkv, d, w, layers[l].cu_seqlens, bud[l % 32]) for l in range(NL)]
@@ -207,6 +209,35 @@ def main():
         sweep["avg%d" % avg] = {"ms_per_step": round(ms, 5), "tokens_per_s": round(n / (ms * 1e-3), 1)}
         del cs
     out["budget_sweep"] = sweep
+
+    # Decode-time re-compression of a grown ragged cache (c6): 32 sequences x 8 KV heads
+    if not args.no_recompress:
+        row = wl.config5_layer_row(inf)
+        bud6 = budgets[row]
+        kept_after_prefill = B.slkv_compacted_sizes(B.Layer(B.SLKV_BF16, 1, Hq, Hkv, d, w, [0, n], bud6,
+                                                            (d, n * d), (d, n * d)))[0]
+        lens = [int(x) + 128 for x in np.diff(kept_after_prefill)]
+        rc = wl.config6(lens, batch=32)
+        call6 = api.RaggedCall("bf16", rc.B, rc.Hq, rc.Hkv, rc.d, rc.w, rc.in_offsets, bud6)
+        q6, k6, v6 = api.to_device(rc.qwin, "bf16"), api.to_device(rc.k_rows, "bf16"), api.to_device(rc.v_rows, "bf16")
+        p6 = torch.from_numpy(rc.pos_in).to(dev)
+        for _ in range(8):
+            call6.run(q6, k6, v6, p6)
+        torch.cuda.synchronize()
+        reps = 64
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call6.run(q6, k6, v6, p6)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rows_in = int(rc.in_offsets[-1])
+        out["recompress"] = {"workload": "c6: 32 sequences x 8 KV heads, cache = kept rows of avg-256 budgets + 128 new tokens, "
+                                         "window 64, bf16 (warm cache: one input set)",
+                             "segments": int(rc.B * rc.Hkv), "rows_in": rows_in, "rows_out": int(call6.total_kept),
+                             "ms_per_call": round(ms, 5), "cached_rows_per_s": round(rows_in / (ms * 1e-3), 1)}
+        del q6, k6, v6, call6
 
     # Stage 1 (Algorithm 1) on the 32 x 32 heads x 16 steps x 16384 attention rows (1 GiB)
     if not args.no_stage1:
