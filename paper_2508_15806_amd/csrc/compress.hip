@@ -34,6 +34,14 @@ struct SegTable {
   int32_t seg_global[kMaxSegPerLaunch];  // index b*Hkv + h
 };
 
+// The same table in device memory, for calls with more segments than fit a kernel argument.
+// chunk_begin and out_off are prefixes over all segments of the call.
+struct SegTableDev {
+  int32_t nseg;
+  int32_t total_chunks;
+  int32_t *tok_begin, *n, *kkeep, *out_off, *head, *qrow_off, *score_off, *chunk_begin, *seg_global;
+};
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
@@ -78,8 +86,8 @@ __device__ __forceinline__ void merge_stats(float& m, float& s, float m2, float 
 constexpr int kTileKeys = 64;
 constexpr int kPrefetch = 2;
 
-template <int DK, int MT, int RB, int PASS>
-__global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(const SegTable tab, const uint16_t* __restrict__ q,
+template <int DK, int MT, int RB, int PASS, class TAB>
+__global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(const TAB tab, const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ kmat, int64_t k_stride_tok,
                                                          int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                          float c_log2, float* __restrict__ part,
@@ -278,8 +286,8 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 // ------------------------------------------------------------------------------------------
 // fp32 scoring with plain FMAs (small shapes).  Same chunking and outputs as the bf16 kernels.
 // PASS 1: thread = query row, K tile in LDS (broadcast reads).  PASS 2: thread = key, Q rows in LDS.
-template <int DK, int PASS>
-__global__ __launch_bounds__(256) void score_f32_kernel(const SegTable tab, const float* __restrict__ q,
+template <int DK, int PASS, class TAB>
+__global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const float* __restrict__ q,
                                                         const float* __restrict__ kmat, int64_t k_stride_tok,
                                                         int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                         float c_log2, float* __restrict__ part,
@@ -354,12 +362,13 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const SegTable tab, cons
 
 // Per-row log-sum-exp (log2 domain) over a segment's chunks.  Block = 16 rows x 16 lanes; lane c
 // folds chunks c, c+16, ... in order, then the 16 partial results are merged by a butterfly.
-__global__ __launch_bounds__(256) void combine_kernel(const SegTable tab, int Rpad, const float* __restrict__ part,
+template <class TAB>
+__global__ __launch_bounds__(256) void combine_kernel(const TAB tab, int Rpad, const float* __restrict__ part,
                                                       float* __restrict__ lse) {
-  const int seg = blockIdx.y;
+  const int seg = blockIdx.x;
   const int c0 = tab.chunk_begin[seg], c1 = tab.chunk_begin[seg + 1];
   if (c0 == c1) return;
-  const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int row = blockIdx.y * 16 + (threadIdx.x >> 4);
   const int cl = threadIdx.x & 15;
   float mm = -INFINITY, ss = 0.f;
   if (row < Rpad) {
@@ -411,8 +420,8 @@ constexpr int kSelCandidates = 3072;   // scores of one first-level digit that t
 
 __device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
 
-template <int RADIUS>   // pooling radius known at compile time (0..3), or -1: any radius, window read from LDS
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab, int w, int pool_kernel, int pool_mode,
+template <int RADIUS, class TAB>   // pooling radius known at compile time (0..3), or -1: any radius, window read from LDS
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
                                                              int write_pooled, const float* __restrict__ imp,
                                                              float* __restrict__ pooled, int32_t* __restrict__ kept_idx,
                                                              int64_t* __restrict__ d_out_offsets, int is_last_group,
@@ -717,7 +726,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SegTable tab,
 }
 
 // Copies kept rows of K and V (bit copies) into the packed output; one 16-byte lane per piece.
-__global__ __launch_bounds__(256) void gather_kernel(const SegTable tab, const GatherArgs ga,
+template <class TAB>
+__global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const GatherArgs ga,
                                                      const int32_t* __restrict__ kept_idx) {
   const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t rel = g / ga.lanes_per_row;
@@ -735,6 +745,25 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable tab, const G
   *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
   *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
   if (ga.pos_out && c == 0) ga.pos_out[row] = ga.pos_in[tok];
+}
+
+// Copies one kernel-argument table (up to kMaxSegPerLaunch segments starting at segment s0) into
+// the device-resident table.  The prefix arrays get one entry more.
+__global__ void table_write_kernel(const SegTable part, int s0, const SegTableDev dst) {
+  const int i = threadIdx.x;
+  if (i < part.nseg) {
+    dst.tok_begin[s0 + i] = part.tok_begin[i];
+    dst.n[s0 + i] = part.n[i];
+    dst.kkeep[s0 + i] = part.kkeep[i];
+    dst.head[s0 + i] = part.head[i];
+    dst.qrow_off[s0 + i] = part.qrow_off[i];
+    dst.score_off[s0 + i] = part.score_off[i];
+    dst.seg_global[s0 + i] = part.seg_global[i];
+  }
+  if (i <= part.nseg) {
+    dst.out_off[s0 + i] = part.out_off[i];
+    dst.chunk_begin[s0 + i] = part.chunk_begin[i];
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -760,8 +789,8 @@ struct Geometry {
 
 struct Plan {
   int R, Rpad, CH;
-  size_t part_bytes, lse_bytes, score_bytes;
-  size_t off_part, off_lse, off_imp, off_pooled, total_bytes;
+  size_t part_bytes, lse_bytes, score_bytes, table_bytes;
+  size_t off_part, off_lse, off_imp, off_pooled, off_table, total_bytes;
 };
 
 static bool seg_ranked(int64_t n, int64_t w, int64_t cap) { return n > w && n > cap && cap > w; }
@@ -788,7 +817,11 @@ static void make_plan(const Geometry& g, Plan& p) {
   p.off_lse = p.off_part + p.part_bytes;
   p.off_imp = p.off_lse + p.lse_bytes;
   p.off_pooled = p.off_imp + p.score_bytes;
-  p.total_bytes = p.off_pooled + p.score_bytes;
+  p.off_table = p.off_pooled + p.score_bytes;
+  // device-resident segment table: only for calls with more segments than one kernel argument holds
+  const size_t S = g.segs.size();
+  p.table_bytes = S > (size_t)kMaxSegPerLaunch ? align((9 * S + 2) * sizeof(int32_t)) : 0;
+  p.total_bytes = p.off_table + p.table_bytes;
 }
 
 static void layer_geometry(const slkv_layer_desc* d, Geometry& g) {
@@ -834,19 +867,19 @@ static void ragged_geometry(const slkv_ragged_desc* d, Geometry& g) {
   }
 }
 
-template <int DK, int MT, int RB>
-static void launch_bf16(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
+template <int DK, int MT, int RB, class TAB>
+static void launch_bf16(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
   if (pass == 1)
-    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 1>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 1, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
                        (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp);
   else
-    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 2>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 2, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
                        (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp);
 }
 
-template <int DK>
-static void launch_bf16_rows(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
+template <int DK, class TAB>
+static void launch_bf16_rows(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                              const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
   if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
   else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
@@ -854,14 +887,15 @@ static void launch_bf16_rows(int pass, int grid, hipStream_t st, const SegTable&
   else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
 }
 
-static void launch_score(int pass, int grid, hipStream_t st, const SegTable& tab, const void* q, const void* k,
+template <class TAB>
+static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                          const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
   if (g.dtype == SLKV_BF16) {
     if (g.d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
     else launch_bf16_rows<64>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
-  hipLaunchKernelGGL((score_f32_kernel<DKV, PS>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
+  hipLaunchKernelGGL((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
                      g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp)
     if (g.d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
     else { if (pass == 1) SLKV_F32_LAUNCH(64, 1); else SLKV_F32_LAUNCH(64, 2); }
@@ -869,24 +903,25 @@ static void launch_score(int pass, int grid, hipStream_t st, const SegTable& tab
   }
 }
 
-template <int RADIUS>
-static hipError_t launch_select_r(int ns, hipStream_t st, const SegTable& tab, const Geometry& g,
+template <int RADIUS, class TAB>
+static hipError_t launch_select_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g,
                                   bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
                                   int64_t* d_out_offsets, int is_last, const GatherArgs& ga) {
   static bool attr_set = false;   // LDS above 64 KB per workgroup has to be requested once per kernel
   const size_t lds = (size_t)(kSelStageFloats + kSelCandidates) * sizeof(float);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS, TAB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((select_kernel<RADIUS>), dim3(ns), dim3(kSelThreads), lds, st, tab, g.w, g.pool_kernel, g.pool,
+  hipLaunchKernelGGL((select_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), lds, st, tab, g.w, g.pool_kernel, g.pool,
                      (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
   return hipSuccess;
 }
 
-static hipError_t launch_select(int ns, hipStream_t st, const SegTable& tab, const Geometry& g, bool write_pooled,
+template <class TAB>
+static hipError_t launch_select(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
                                 const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets, int is_last,
                                 const GatherArgs& ga) {
   const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
@@ -953,36 +988,9 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
   ga.pos_in = d_pos_in;
   ga.pos_out = d_pos_out;
 
-  int64_t out_run = 0;
-  for (int64_t s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
-    SegTable tab;
-    std::memset(&tab, 0, sizeof(tab));
-    const int ns = (int)std::min<int64_t>(kMaxSegPerLaunch, S - s0);
-    tab.nseg = ns;
-    int chunks = 0;
-    for (int i = 0; i < ns; ++i) {
-      const Seg& sg = g.segs[(size_t)(s0 + i)];
-      tab.tok_begin[i] = (int32_t)sg.row_begin;
-      tab.n[i] = (int32_t)sg.n;
-      const bool all = sg.n <= g.w || sg.n <= sg.cap;
-      tab.kkeep[i] = all ? -1 : (int32_t)std::min<int64_t>(std::max<int64_t>(sg.cap - g.w, 0), sg.n - g.w);
-      tab.out_off[i] = (int32_t)out_run;
-      out_run += kept_rows(sg.n, g.w, sg.cap);
-      tab.head[i] = sg.head;
-      tab.qrow_off[i] = (int32_t)sg.qrow_off;
-      tab.score_off[i] = (int32_t)sg.score_off;
-      tab.chunk_begin[i] = chunks;
-      tab.seg_global[i] = (int32_t)(s0 + i);
-      if (seg_ranked(sg.n, g.w, sg.cap)) chunks += (int)((sg.n - g.w + p.CH - 1) / p.CH);
-    }
-    tab.out_off[ns] = (int32_t)out_run;
-    tab.chunk_begin[ns] = chunks;
-    tab.total_chunks = chunks;
-    // the remaining entries repeat the end values so that searches stay inside the table
-    for (int i = ns + 1; i <= kMaxSegPerLaunch; ++i) {
-      tab.out_off[i] = tab.out_off[ns];
-      tab.chunk_begin[i] = chunks;
-    }
+  // One launch group: the kernels of the pass over the segments one table describes.
+  auto launch_group = [&](const auto& tab, int ns, int chunks, int is_last, bool any_large, int64_t rows) -> slkv_status {
+    using TAB = std::decay_t<decltype(tab)>;
     if (chunks > 0) {
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_STATS, st);
@@ -990,7 +998,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
       }
       {
         ScopedKernelTimer tm(SLKV_K_COMBINE, st);
-        hipLaunchKernelGGL(combine_kernel, dim3((p.Rpad + 15) / 16, ns), dim3(256), 0, st, tab, p.Rpad, part, lse);
+        hipLaunchKernelGGL(combine_kernel<TAB>, dim3(ns, (p.Rpad + 15) / 16), dim3(256), 0, st, tab, p.Rpad, part, lse);
       }
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_ACCUM, st);
@@ -999,20 +1007,85 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
     }
     {
       ScopedKernelTimer tm(SLKV_K_SELECT, st);
-      hipError_t se = launch_select(ns, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets,
-                                    (int)(s0 + ns == S), ga);
+      hipError_t se = launch_select(ns, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets, is_last, ga);
       if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
     }
-    const int64_t rows = (int64_t)tab.out_off[ns] - tab.out_off[0];
-    bool any_large = false;
-    for (int i = 0; i < ns; ++i) any_large |= tab.out_off[i + 1] - tab.out_off[i] > kInlineGatherRows;
     if (any_large) {
       ScopedKernelTimer tm(SLKV_K_GATHER, st);
       const int64_t threads = rows * lanes_per_row;
-      hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx);
+      hipLaunchKernelGGL(gather_kernel<TAB>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return SLKV_OK;
+  };
+
+  // Few segments: the table travels as a kernel argument.  More: the per-64 tables are written
+  // to a device-resident table by a small kernel each, and one launch group covers all segments.
+  const bool dev_table = S > kMaxSegPerLaunch;
+  SegTableDev dev;
+  std::memset(&dev, 0, sizeof(dev));
+  if (dev_table) {
+    int32_t* t = (int32_t*)(ws + p.off_table);
+    dev.tok_begin = t; t += S;
+    dev.n = t; t += S;
+    dev.kkeep = t; t += S;
+    dev.head = t; t += S;
+    dev.qrow_off = t; t += S;
+    dev.score_off = t; t += S;
+    dev.seg_global = t; t += S;
+    dev.out_off = t; t += S + 1;
+    dev.chunk_begin = t;
+    dev.nseg = (int32_t)S;
+  }
+  int64_t out_run = 0, chunks_run = 0;
+  bool any_large_all = false;
+  for (int64_t s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
+    SegTable tab;
+    std::memset(&tab, 0, sizeof(tab));
+    const int ns = (int)std::min<int64_t>(kMaxSegPerLaunch, S - s0);
+    tab.nseg = ns;
+    int64_t chunks = dev_table ? chunks_run : 0;   // the device table holds prefixes over the whole call
+    const int64_t rows_begin = out_run;
+    bool any_large = false;
+    for (int i = 0; i < ns; ++i) {
+      const Seg& sg = g.segs[(size_t)(s0 + i)];
+      tab.tok_begin[i] = (int32_t)sg.row_begin;
+      tab.n[i] = (int32_t)sg.n;
+      const bool all = sg.n <= g.w || sg.n <= sg.cap;
+      tab.kkeep[i] = all ? -1 : (int32_t)std::min<int64_t>(std::max<int64_t>(sg.cap - g.w, 0), sg.n - g.w);
+      tab.out_off[i] = (int32_t)out_run;
+      const int64_t kept = kept_rows(sg.n, g.w, sg.cap);
+      any_large |= kept > kInlineGatherRows;
+      out_run += kept;
+      tab.head[i] = sg.head;
+      tab.qrow_off[i] = (int32_t)sg.qrow_off;
+      tab.score_off[i] = (int32_t)sg.score_off;
+      tab.chunk_begin[i] = (int32_t)chunks;
+      tab.seg_global[i] = (int32_t)(s0 + i);
+      if (seg_ranked(sg.n, g.w, sg.cap)) chunks += (sg.n - g.w + p.CH - 1) / p.CH;
+    }
+    if (chunks >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "too many key chunks");
+    tab.out_off[ns] = (int32_t)out_run;
+    tab.chunk_begin[ns] = (int32_t)chunks;
+    tab.total_chunks = (int32_t)chunks;
+    // the remaining entries repeat the end values so that searches stay inside the table
+    for (int i = ns + 1; i <= kMaxSegPerLaunch; ++i) {
+      tab.out_off[i] = tab.out_off[ns];
+      tab.chunk_begin[i] = (int32_t)chunks;
+    }
+    if (dev_table) {
+      hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kMaxSegPerLaunch + 64), 0, st, tab, (int)s0, dev);
+      chunks_run = chunks;
+      any_large_all |= any_large;
+    } else {
+      slkv_status gs = launch_group(tab, ns, (int)chunks, 1, any_large, out_run - rows_begin);
+      if (gs != SLKV_OK) return gs;
+    }
+  }
+  if (dev_table) {
+    dev.total_chunks = (int32_t)chunks_run;
+    return launch_group(dev, (int)S, (int)chunks_run, 1, any_large_all, out_run);
   }
   return SLKV_OK;
 }

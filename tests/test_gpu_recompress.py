@@ -92,3 +92,15 @@ def test_config6_shape_sample():
     rc = wl.config6(lens, batch=3)
     rep = check(rc, bud)
     assert rep["segments"] == 24
+
+
+def test_hundreds_of_segments_use_the_device_resident_table():
+    rng = np.random.default_rng(11)
+    Hkv, Bn, w = 4, 75, 16                                     # 300 segments
+    lens = rng.integers(0, 700, size=Bn * Hkv)
+    lens[::17] = 0
+    lens[5::23] = w
+    rc = wl.make_ragged_cache((206,), lens.tolist(), Bn, 8, Hkv, 64, w, dtype="bf16", bias_frac=0.04)
+    bud = np.array([60, 300, 16, 128], dtype=np.int32)
+    rep = check(rc, bud)
+    assert rep["segments"] == 300 and rep["ranked"] > 100
