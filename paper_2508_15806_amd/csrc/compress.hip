@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <type_traits>
@@ -907,13 +908,18 @@ template <int RADIUS, class TAB>
 static hipError_t launch_select_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g,
                                   bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
                                   int64_t* d_out_offsets, int is_last, const GatherArgs& ga) {
-  static bool attr_set = false;   // LDS above 64 KB per workgroup has to be requested once per kernel
+  // LDS above 64 KB per workgroup has to be requested once per kernel and device
+  static std::atomic<uint64_t> attr_set{0};
   const size_t lds = (size_t)(kSelStageFloats + kSelCandidates) * sizeof(float);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS, TAB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev < 64 ? (uint64_t(1) << dev) : 0;
+  if (!(attr_set.load(std::memory_order_relaxed) & bit)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS, TAB>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.fetch_or(bit, std::memory_order_relaxed);
   }
   hipLaunchKernelGGL((select_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), lds, st, tab, g.w, g.pool_kernel, g.pool,
                      (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);

@@ -1,6 +1,7 @@
 // Optional per-kernel timing with HIP events (slkv_profile_begin / slkv_profile_end).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -12,7 +13,7 @@ struct Rec {
   hipEvent_t a, b;
 };
 std::mutex g_mu;
-bool g_on = false;
+std::atomic<bool> g_on{false};   // read without the lock on the launch path
 std::vector<Rec> g_pool;   // events created by slkv_profile_begin
 size_t g_used = 0;
 }  // namespace
@@ -20,8 +21,9 @@ size_t g_used = 0;
 namespace slkv {
 
 ScopedKernelTimer::ScopedKernelTimer(int id, void* stream) : slot_(-1), stream_(stream) {
+  if (!g_on.load(std::memory_order_relaxed)) return;
   std::lock_guard<std::mutex> lk(g_mu);
-  if (!g_on || g_used >= g_pool.size()) return;
+  if (!g_on.load(std::memory_order_relaxed) || g_used >= g_pool.size()) return;
   slot_ = (int)g_used++;
   g_pool[slot_].id = id;
   (void)hipEventRecord(g_pool[slot_].a, (hipStream_t)stream_);

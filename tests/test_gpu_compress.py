@@ -54,7 +54,8 @@ def test_config2_bf16():
 
 
 @pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 16, 128), (4, 2, 16, 128), (8, 2, 16, 128), (8, 2, 32, 128),
-                                        (16, 2, 32, 128), (4, 4, 24, 64), (8, 2, 20, 64), (32, 8, 16, 64)])
+                                        (16, 2, 32, 128), (4, 4, 24, 64), (8, 2, 20, 64), (32, 8, 16, 64),
+                                        (16, 2, 64, 128), (16, 2, 64, 64), (8, 1, 48, 128), (8, 2, 64, 64)])
 def test_bf16_row_shapes_and_ragged_tails(Hq, Hkv, w, d):
     # lengths chosen so that the history is not a multiple of the 32-key MFMA tile
     lay = wl.make_layer((101, Hq, w, d), [1000 + w + 7, 333 + w], Hq, Hkv, d, w, dtype="bf16", bias_frac=0.03)
