@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-recompress", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other budgets of the sweep")
-    ap.add_argument("--cpu-layers", type=int, default=8, help="layers the CPU oracle is timed on")
+    ap.add_argument("--cpu-layers", type=int, default=32, help="layers the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()

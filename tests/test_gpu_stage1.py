@@ -79,3 +79,26 @@ def test_two_runs_are_bit_identical():
     a = run(nr.rows, nr.needle_start, nr.needle_len, nr.topk)
     b = run(nr.rows, nr.needle_start, nr.needle_len, nr.topk)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_config4_full_launch_shape_sampled_heads():
+    # the benchmark's launch configuration (32 x 32 heads x 16 rows of 16384 weights = 1 GiB, one
+    # workgroup per row); 8 generated layers are repeated four times on the device, and a sample
+    # of heads is checked against the oracle
+    import torch
+    nr = wl.config4(L=8)
+    d_rows = torch.from_numpy(nr.rows).cuda().repeat(4, 1, 1, 1)
+    assert tuple(d_rows.shape) == (32, 32, 16, 16384)
+    acc_d, sc_d = api.score_heads(d_rows, nr.needle_start, nr.needle_len, nr.topk)
+    torch.cuda.synchronize()
+    acc, scores = acc_d.cpu().numpy(), sc_d.cpu().numpy()
+    rng = np.random.default_rng(5)
+    picks = {(int(l), int(h)) for l, h in zip(rng.integers(0, 32, 40), rng.integers(0, 32, 40))}
+    # heads whose rows touch the needle are the interesting ones: add those with the largest WO
+    top = np.argsort(acc[..., 0].ravel())[-8:]
+    picks |= {(int(i // 32), int(i % 32)) for i in top}
+    for l, h in sorted(picks):
+        racc, rsc = oracle.score_heads(nr.rows[l % 8:l % 8 + 1, h:h + 1], nr.needle_start, nr.needle_len, nr.topk)
+        np.testing.assert_allclose(acc[l, h], racc[0, 0], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(scores[l, h], rsc[0, 0], rtol=1e-11, atol=1e-15)
+    assert (acc[..., 4] == 16).all()
