@@ -293,10 +293,13 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
                                                         int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                         float c_log2, float* __restrict__ part,
                                                         const float* __restrict__ lse, float* __restrict__ imp) {
-  constexpr int TROWS = 32;
+  constexpr int TROWS = 32;                 // keys (pass 1) or query rows (pass 2) per LDS tile
+  constexpr int NSUB = 256 / TROWS;         // thread = (lane32, sub): 32 rows x 8 key subsets, or 32 keys x 8 row subsets
   __shared__ __attribute__((aligned(16))) float tile[TROWS][DK];
   __shared__ float lse_s[TROWS];
+  __shared__ float2 red[NSUB][TROWS];
   const int tid = threadIdx.x;
+  const int l32 = tid & (TROWS - 1), sub = tid / TROWS;
   const int bid = blockIdx.x;
   const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
   const int chunk = bid - tab.chunk_begin[seg];
@@ -307,8 +310,9 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
   const float* qbase = q + (int64_t)tab.qrow_off[seg] * DK;
 
   if (PASS == 1) {
-    for (int r0 = 0; r0 < R; r0 += 256) {
-      const int row = r0 + tid;
+    // 32 query rows at a time; the thread's key subset is keys sub, sub + 8, ... of every tile
+    for (int r0 = 0; r0 < Rpad; r0 += TROWS) {
+      const int row = r0 + l32;
       float qr[DK];
 #pragma unroll
       for (int p = 0; p < DK; ++p) qr[p] = row < R ? qbase[(int64_t)row * DK + p] : 0.f;
@@ -320,22 +324,39 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
           tile[kr][p] = k0 + kr < key_end ? kbase[(int64_t)(k0 + kr) * k_stride_tok + p] : 0.f;
         }
         __syncthreads();
-        const int cnt = min(TROWS, key_end - k0);
-        for (int kr = 0; kr < cnt; ++kr) {
+        float x[TROWS / NSUB];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < TROWS / NSUB; ++i) {
+          const int kr = sub + i * NSUB;
           float acc = 0.f;
 #pragma unroll
           for (int p = 0; p < DK; ++p) acc = fmaf(qr[p], tile[kr][p], acc);
-          merge_stats(mm, ss, acc * c_log2, 1.f);
+          x[i] = k0 + kr < key_end ? acc * c_log2 : -INFINITY;
+          mx = fmaxf(mx, x[i]);
         }
+        const float mn = fmaxf(mm, mx);
+        const float mu = mn == -INFINITY ? 0.f : mn;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < TROWS / NSUB; ++i) sum += fast_exp2(x[i] - mu);
+        ss = ss * fast_exp2(mm - mu) + sum;
+        mm = mn;
       }
-      if (row < Rpad) {
+      __syncthreads();
+      red[sub][l32] = make_float2(mm, ss);
+      __syncthreads();
+      if (sub == 0) {
+#pragma unroll
+        for (int k2 = 1; k2 < NSUB; ++k2) merge_stats(mm, ss, red[k2][l32].x, red[k2][l32].y);
         part[((int64_t)bid * Rpad + row) * 2 + 0] = row < R ? mm : -INFINITY;
         part[((int64_t)bid * Rpad + row) * 2 + 1] = row < R ? ss : 0.f;
       }
     }
   } else {
-    for (int k0 = key_begin; k0 < key_end; k0 += 256) {
-      const int key = k0 + tid;
+    // 32 keys at a time; the thread's row subset is rows sub, sub + 8, ... of every query tile
+    for (int k0 = key_begin; k0 < key_end; k0 += TROWS) {
+      const int key = k0 + l32;
       float kr[DK];
 #pragma unroll
       for (int p = 0; p < DK; ++p) kr[p] = key < key_end ? kbase[(int64_t)key * k_stride_tok + p] : 0.f;
@@ -348,15 +369,23 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
         }
         if (tid < TROWS) lse_s[tid] = r0 + tid < R ? lse[seg * Rpad + r0 + tid] : INFINITY;
         __syncthreads();
-        const int cnt = min(TROWS, R - r0);
-        for (int rr = 0; rr < cnt; ++rr) {
+#pragma unroll
+        for (int i = 0; i < TROWS / NSUB; ++i) {
+          const int rr = sub + i * NSUB;
           float acc = 0.f;
 #pragma unroll
           for (int p = 0; p < DK; ++p) acc = fmaf(tile[rr][p], kr[p], acc);
-          colsum += fast_exp2(fmaf(acc, c_log2, -lse_s[rr]));
+          colsum += fast_exp2(fmaf(acc, c_log2, -lse_s[rr]));   // rows past R: exp2(-inf) = 0
         }
       }
-      if (key < key_end) imp[tab.score_off[seg] + key] = colsum;
+      __syncthreads();
+      red[sub][l32].x = colsum;
+      __syncthreads();
+      if (sub == 0) {
+#pragma unroll
+        for (int k2 = 1; k2 < NSUB; ++k2) colsum += red[k2][l32].x;
+        if (key < key_end) imp[tab.score_off[seg] + key] = colsum;
+      }
     }
   }
 }
@@ -804,8 +833,13 @@ static void make_plan(const Geometry& g, Plan& p) {
   for (const Seg& s : g.segs)
     if (seg_ranked(s.n, g.w, s.cap)) keys += s.n - g.w;
   int64_t ch = (keys + 511) / 512;
-  ch = (ch + 127) / 128 * 128;
-  ch = std::max<int64_t>(256, std::min<int64_t>(ch, 1 << 16));
+  if (g.dtype == SLKV_BF16) {                 // MFMA kernels: pairs of 64-key tiles
+    ch = (ch + 127) / 128 * 128;
+    ch = std::max<int64_t>(256, std::min<int64_t>(ch, 1 << 16));
+  } else {                                    // fp32 kernels: 32-key tiles
+    ch = (ch + 31) / 32 * 32;
+    ch = std::max<int64_t>(32, std::min<int64_t>(ch, 1 << 16));
+  }
   p.CH = (int)ch;
   int64_t chunks = 0;
   for (const Seg& s : g.segs)
