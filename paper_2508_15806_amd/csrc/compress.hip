@@ -175,11 +175,13 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   }
 
   // one tile: registers -> LDS, refill the register slot, barrier, MFMAs + epilogue
-  auto do_tile = [&](int t, u32x4 (&pf)[LPT], auto masked_c) __attribute__((always_inline)) {
+  auto do_tile = [&](int t, u32x4 (&pf)[LPT], auto masked_c, auto online_c, auto first_c) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_c)::value;   // the tile may reach past key_end
+    constexpr bool ONLINE = decltype(online_c)::value;   // pass 1: running maximum instead of a fixed reference
+    constexpr bool FIRST = decltype(first_c)::value;     // pass 1: the chunk's first tile (fixes the reference)
     const int buf = t & 1;
     store_tile(pf, buf);
-    issue_tile(t + NPF, pf);   // past the chunk end every piece comes from one clamped row
+    if (!ONLINE) issue_tile(t + NPF, pf);   // past the chunk end every piece comes from one clamped row
     __syncthreads();
     if (PASS == 2 && t > 0 && tid < TK) {          // column sums of the previous tile
       float v = 0.f;
@@ -220,16 +222,33 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
             for (int i = 0; i < 16; ++i)
               if (key0 + 8 * (i >> 2) + 4 * half + (i & 3) >= key_end) acc[i] = -INFINITY;
           }
-          float mx = fmaxf(acc[0], acc[1]);
+          if (ONLINE) {
+            float mx = fmaxf(acc[0], acc[1]);
 #pragma unroll
-          for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(acc[i], acc[i + 1]));
-          const float mn = fmaxf(m_run[mt], mx * c_log2);
-          const float mu = mn == -INFINITY ? 0.f : mn;
-          float sum = 0.f;
+            for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(acc[i], acc[i + 1]));
+            const float mn = fmaxf(m_run[mt], mx * c_log2);
+            const float mu = mn == -INFINITY ? 0.f : mn;
+            float sum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c_log2, -mu));
-          s_run[mt] = s_run[mt] * fast_exp2(m_run[mt] - mu) + sum;
-          m_run[mt] = mn;
+            for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c_log2, -mu));
+            s_run[mt] = s_run[mt] * fast_exp2(m_run[mt] - mu) + sum;
+            m_run[mt] = mn;
+          } else {
+            // The reference of the exponentials is fixed by the lane's first 16 logits of the chunk
+            // (any finite reference gives the same log-sum-exp); later logits may exceed it by up to
+            // ~2^100 before the sum overflows, which the caller detects and repeats ONLINE.
+            if (FIRST && sb == 0) {
+              float mx = fmaxf(acc[0], acc[1]);
+#pragma unroll
+              for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(acc[i], acc[i + 1]));
+              const float mn = mx * c_log2;
+              m_run[mt] = mn == -INFINITY ? 0.f : mn;
+            }
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c_log2, -m_run[mt]));
+            s_run[mt] += sum;
+          }
         } else {
           // lane: key key0 + l32, query rows mt*32 + 8*(i/4) + 4*half + i%4
 #pragma unroll
@@ -246,12 +265,51 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   // everything loaded so far (first two tiles, Q, lse) has to be complete here; inside the loop
   // only the two tile slots stay in flight, so the waits there can be partial
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-  for (int t0 = 0; t0 < ntiles - NPF; t0 += NPF) {
-    do_tile(t0, pf0, std::false_type{});
-    do_tile(t0 + 1, pf1, std::false_type{});
+  using T = std::true_type;
+  using F = std::false_type;
+  if (PASS == 1) {
+    // the first tile fixes the reference of the exponentials; only the last pair can reach past the chunk end
+    if (ntiles > NPF) {
+      do_tile(0, pf0, F{}, F{}, T{});
+      do_tile(1, pf1, F{}, F{}, F{});
+      for (int t0 = NPF; t0 < ntiles - NPF; t0 += NPF) {
+        do_tile(t0, pf0, F{}, F{}, F{});
+        do_tile(t0 + 1, pf1, F{}, F{}, F{});
+      }
+      do_tile(ntiles - 2, pf0, T{}, F{}, F{});
+      do_tile(ntiles - 1, pf1, T{}, F{}, F{});
+    } else {
+      do_tile(0, pf0, T{}, F{}, T{});
+      do_tile(1, pf1, T{}, F{}, F{});
+    }
+  } else {
+    for (int t0 = 0; t0 < ntiles - NPF; t0 += NPF) {
+      do_tile(t0, pf0, F{}, F{}, F{});
+      do_tile(t0 + 1, pf1, F{}, F{}, F{});
+    }
+    do_tile(ntiles - 2, pf0, T{}, F{}, F{});
+    do_tile(ntiles - 1, pf1, T{}, F{}, F{});
   }
-  do_tile(ntiles - 2, pf0, std::true_type{});   // only the last pair can reach past the chunk end
-  do_tile(ntiles - 1, pf1, std::true_type{});
+
+  if (PASS == 1) {
+    // A sum that left the fp32 range (logits far above the chunk's first ones): the whole
+    // workgroup repeats the chunk with the running maximum.  Not taken for ordinary inputs.
+    bool bad = false;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) bad = bad || !(s_run[mt] < INFINITY);
+    if (__syncthreads_or(bad ? 1 : 0)) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        m_run[mt] = -INFINITY;
+        s_run[mt] = 0.f;
+      }
+      for (int t = 0; t < ntiles; ++t) {          // plain loop, one tile in flight: this path is rare
+        issue_tile(t, pf0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        do_tile(t, pf0, T{}, T{}, F{});
+      }
+    }
+  }
 
   if (PASS == 2) {
     __syncthreads();

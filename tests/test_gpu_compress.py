@@ -167,3 +167,23 @@ def test_config5_ragged_long_context():
     print("c5: segments %d ranked %d exact %d tolerant %d max_rel %.3g" % (
         rep["segments"], rep["ranked"], rep["exact"], rep["tolerant"], rep["max_rel"]), flush=True)
     assert rep["segments"] == 32
+
+
+def test_extreme_logits_take_the_running_maximum_path():
+    # The first 64 history keys of every head are zero and the later ones are large and aligned with
+    # the queries: their logits exceed the first ones by far more than fp32 exponent range allows
+    # for a sum referenced to the first logits, so the statistics pass has to repeat its chunk
+    # with the running maximum.  The softmax then concentrates on the late keys.
+    w, Hq, Hkv, d = 16, 4, 2, 128
+    lay = wl.make_layer((112,), [1200, 300], Hq, Hkv, d, w, dtype="bf16")
+    three = wl.to_bf16_bits(np.full((d,), 3.0, dtype=np.float32))
+    small = wl.to_bf16_bits(np.random.default_rng(1).standard_normal((Hkv, 1500, d)).astype(np.float32) * 0.01)
+    lay.qwin[:] = three
+    lay.k[:] = small
+    lay.k[:, 500:560, :] = three            # logits 9 * 128 / sqrt(128) = 101.8 nats = 146.9 in base 2
+    lay.k[:, 1200:1264, :] = 0              # second sequence: zero keys first, then large ones
+    lay.k[:, 1300:1360, :] = three
+    # capacities below the number of large keys: everything else underflows in fp32 on the GPU
+    # (its true weight is about e^-100), so only the large keys can be ranked
+    rep = check(lay, np.array([w + 50, w + 8], dtype=np.int32))
+    assert rep["ranked"] == 4
