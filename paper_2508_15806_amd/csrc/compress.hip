@@ -324,6 +324,10 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   } else {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
+      // (reference, sum) -> (log-sum-exp, 1): a sum referenced to early logits can be very large
+      // or small, and merging such pairs directly could lose it to an underflowing factor
+      m_run[mt] = s_run[mt] > 0.f ? m_run[mt] + __builtin_amdgcn_logf(s_run[mt]) : -INFINITY;
+      s_run[mt] = 1.f;
       float m2 = __shfl_xor(m_run[mt], 32, 64);
       float s2 = __shfl_xor(s_run[mt], 32, 64);
       merge_stats(m_run[mt], s_run[mt], m2, s2);
