@@ -212,7 +212,7 @@ slkv_status slkv_recompress_layer(const slkv_ragged_desc* desc, const void* d_qw
  * order and sets *count to the number recorded.  Process-wide; not meant for production.
  */
 typedef enum {
-  SLKV_K_SCORE_STATS = 0,   /* logits + per-row running max / sum-exp */
+  SLKV_K_SCORE_STATS = 0,   /* logits + per-row sum-exp of every key chunk */
   SLKV_K_COMBINE = 1,       /* per-row log-sum-exp over the key chunks */
   SLKV_K_SCORE_ACCUM = 2,   /* logits + exp(logit - lse) summed down the rows */
   SLKV_K_SELECT = 3,        /* pooling + top-k */

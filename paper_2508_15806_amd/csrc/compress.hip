@@ -1,5 +1,5 @@
 // Stage 2b of SurfaceLogicKV (Section 3.4, Eq. 7-8, Algorithm 3) on gfx950:
-//   pass 1  score_*<.., 1>  window-query x history-key logits, per-row running max / sum-exp
+//   pass 1  score_*<.., 1>  window-query x history-key logits, per-row (reference, sum-exp) per key chunk
 //   combine                  per-row log-sum-exp over the key chunks
 //   pass 2  score_*<.., 2>  logits again, exp(logit - lse) summed down the G*w rows -> importance
 //   select                   1-D pooling + per-head top-k (radix select, ordered compaction)
@@ -81,7 +81,7 @@ __device__ __forceinline__ void merge_stats(float& m, float& s, float m2, float 
 // ks, ks+KS, .. of every tile.  The 32x32x16 MFMA takes, per lane, 8 consecutive k-elements of
 // row (lane%32) at k offset 8*(lane/32) for both operands, and returns in result register i the
 // element at row 8*(i/4) + 4*(lane/32) + i%4, column lane%32.
-//   PASS 1: D[key][qrow]: a lane owns one query row per MFMA tile -> running (max, sum-exp).
+//   PASS 1: D[key][qrow]: a lane owns one query row per MFMA tile -> sum of exp2(x - reference).
 //   PASS 2: D[qrow][key]: a lane owns one key column -> sum over rows of exp2(x - lse[row]).
 // Rows beyond R and keys beyond the chunk are loaded from a clamped (valid) address and masked.
 constexpr int kTileKeys = 64;
