@@ -688,7 +688,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
     const int shift = nbits > 11 ? nbits - 11 : 0;
     if (use_list && ncand <= kSelRankMax) {
       // short list: the k-th largest by counting, for each entry, the entries above it
-      if (tid < ncand) {
+      if ((uint32_t)tid < ncand) {
         const uint32_t kv = cand[tid];
         uint32_t gt = 0, ge = 0;
         for (uint32_t i = 0; i < ncand; ++i) {

@@ -55,3 +55,50 @@ def test_captured_call_replays_like_eager():
             got = outputs(call)
             for a, b in zip(got, refs[i]):
                 assert np.array_equal(a, b), (rep, i)
+
+
+def test_captured_ragged_call_with_device_table_replays_like_eager():
+    # more than 64 segments: the call also launches the small kernels that write the segment table
+    import torch
+    rng = np.random.default_rng(3)
+    Hkv, Bn, w, d, Hq = 4, 24, 16, 64, 8                         # 96 segments
+    lens = rng.integers(w + 1, 500, size=Bn * Hkv).tolist()
+    rcs = [wl.make_ragged_cache((302, i), lens, Bn, Hq, Hkv, d, w, dtype="bf16", bias_frac=0.04) for i in range(2)]
+    bud = np.array([60, 200, 16, 100], dtype=np.int32)
+    call = api.RaggedCall("bf16", Bn, Hq, Hkv, d, w, rcs[0].in_offsets, bud)
+    q = api.to_device(rcs[0].qwin, "bf16")
+    k = api.to_device(rcs[0].k_rows, "bf16")
+    v = api.to_device(rcs[0].v_rows, "bf16")
+    pos = torch.from_numpy(rcs[0].pos_in).cuda()
+
+    def load(rc):
+        q.copy_(api.to_device(rc.qwin, "bf16")); k.copy_(api.to_device(rc.k_rows, "bf16")); v.copy_(api.to_device(rc.v_rows, "bf16"))
+        pos.copy_(torch.from_numpy(rc.pos_in).cuda())
+
+    def outs():
+        return [api.to_host(call.k_out).copy(), call.kept_idx.cpu().numpy().copy(), call.pos_out.cpu().numpy().copy()]
+    refs = []
+    for rc in rcs:
+        load(rc)
+        call.run(q, k, v, pos)
+        torch.cuda.synchronize()
+        refs.append(outs())
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        call.run(q, k, v, pos)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        call.run(q, k, v, pos)
+    for rep in range(2):
+        for i, rc in enumerate(rcs):
+            load(rc)
+            call.kept_idx.fill_(-1)
+            call.workspace.zero_()                               # the table in the workspace is rewritten by the replay
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for a, b in zip(outs(), refs[i]):
+                assert np.array_equal(a, b), (rep, i)
