@@ -53,14 +53,24 @@ union Pack16 {
   bf16x8 b;
 };
 
-__device__ __forceinline__ int find_segment(const int32_t* prefix, int nseg, int x) {
-  // largest s with prefix[s] <= x, prefix non-decreasing, prefix[nseg] > x
-  int lo = 0, hi = nseg - 1;
+// Segment of a block / row: the largest s with prefix[s] <= x (prefix non-decreasing, prefix[nseg] > x).
+// Device-resident table: binary search.
+__device__ __forceinline__ int find_segment(const SegTableDev& tab, const int32_t* prefix, int x) {
+  int lo = 0, hi = tab.nseg - 1;
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
     if (prefix[mid] <= x) lo = mid; else hi = mid - 1;
   }
   return lo;
+}
+// Kernel-argument table: count the entries <= x.  The loads do not depend on one another, so the
+// lookup costs one scalar-load latency at the start of the kernel instead of one per search step
+// (entries past nseg repeat the end value, which is > x).
+__device__ __forceinline__ int find_segment(const SegTable&, const int32_t (&prefix)[kMaxSegPerLaunch + 1], int x) {
+  int s = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxSegPerLaunch; ++i) s += prefix[i] <= x ? 1 : 0;
+  return s;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -101,7 +111,7 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   constexpr int CPR = DK * 2 / 16;         // 16-byte pieces per key row
   constexpr int LPT = TK * CPR / 256;      // pieces per thread per tile
   constexpr int NPF = kPrefetch;
-  static_assert(TK * CPR % 256 == 0, "tile must divide over the workgroup");
+  static_assert(TK * CPR % 256 == 0 && LPT < 16, "tile must divide over the workgroup; LPT is or-ed into a wait count");
   __shared__ __attribute__((aligned(16))) unsigned char ktile[2][TK * ROWB];
   __shared__ float red[2][RB][TK];
   __shared__ float2 comb[KS][RB * 32 * MT];
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   const int l32 = lane & 31, half = lane >> 5;
 
   const int bid = blockIdx.x;
-  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
+  const int seg = find_segment(tab, tab.chunk_begin, bid);
   const int chunk = bid - tab.chunk_begin[seg];
   const int m = tab.n[seg] - w;
   const int key_begin = chunk * CH;
@@ -142,8 +152,7 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
     }
   };
   static_assert(NPF == 2, "the tile loop below is written out for two register slots");
-  issue_tile(0, pf0);
-  issue_tile(1, pf1);
+  issue_tile(0, pf0);   // the second tile is requested after the queries: the loop can start without it
 
   // query rows of this wave, kept in registers for the whole chunk
   bf16x8 qreg[MT][KK];
@@ -157,15 +166,14 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
       qreg[mt][kk] = p.b;
     }
   }
+  // pass 2: the log-sum-exp of the workgroup's rows, one coalesced load per thread here, handed
+  // to the lanes through LDS once the loads have landed
+  constexpr int NLSE = (RB * 32 * MT + 255) / 256;
+  float lse_ld[PASS == 2 ? NLSE : 1];
   float lse_r[PASS == 2 ? MT : 1][16];
   if (PASS == 2) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rb * 32 * MT + mt * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-        lse_r[mt][i] = row < R ? lse[seg * Rpad + row] : INFINITY;
-      }
+    for (int j = 0; j < NLSE; ++j) lse_ld[j] = lse[seg * Rpad + min(tid + j * 256, Rpad - 1)];
   }
   float m_run[MT], s_run[MT];
 #pragma unroll
@@ -262,9 +270,25 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
     }
   };
 
-  // everything loaded so far (first two tiles, Q, lse) has to be complete here; inside the loop
-  // only the two tile slots stay in flight, so the waits there can be partial
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  // The first tile, Q and lse have to be complete here (loads return in order; the LPT loads of
+  // the second tile, issued last, may still be in flight); inside the loop only the two tile slots
+  // stay in flight, so the waits there can be partial.
+  __builtin_amdgcn_sched_barrier(0);          // keep every earlier load ahead of the second tile's
+  issue_tile(1, pf1);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | LPT);   // vmcnt(LPT)
+  __builtin_amdgcn_sched_barrier(0);
+  if (PASS == 2) {
+    float* lse_s = reinterpret_cast<float*>(&comb[0][0]);   // comb is used by pass 1 only
+    static_assert(sizeof(comb) >= NLSE * 256 * sizeof(float), "comb holds one value per thread and load");
+#pragma unroll
+    for (int j = 0; j < NLSE; ++j) lse_s[tid + j * 256] = tid + j * 256 < R ? lse_ld[j] : INFINITY;
+    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        lse_r[mt][i] = lse_s[rb * 32 * MT + mt * 32 + 8 * (i >> 2) + 4 * half + (i & 3)];
+  }
   using T = std::true_type;
   using F = std::false_type;
   if (PASS == 1) {
@@ -363,7 +387,7 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
   const int tid = threadIdx.x;
   const int l32 = tid & (TROWS - 1), sub = tid / TROWS;
   const int bid = blockIdx.x;
-  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
+  const int seg = find_segment(tab, tab.chunk_begin, bid);
   const int chunk = bid - tab.chunk_begin[seg];
   const int m = tab.n[seg] - w;
   const int key_begin = chunk * CH;
@@ -827,7 +851,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const Gather
   const int64_t row0 = tab.out_off[0], row1 = tab.out_off[tab.nseg];
   const int64_t row = row0 + rel;
   if (row >= row1) return;
-  const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
+  const int seg = find_segment(tab, tab.out_off, (int)row);
   if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by select_kernel
   const int64_t tok = (int64_t)tab.tok_begin[seg] + kept_idx[row];
   const int64_t h = tab.head[seg];
