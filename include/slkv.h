@@ -11,12 +11,14 @@
  *   Stage 2b (Section 3.4, Eq. 7-8, Algorithm 3): at prefill, per layer and head, score the
  *     history keys against the last window of queries, keep the top-ranked history entries
  *     within the capacity plus the whole window                      -> slkv_compress_layer
+ *     The same selection on a cache that is already compacted and has grown during generation
+ *     (heads of different lengths)                                   -> slkv_recompress_layer
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every
  *     buffer; the library allocates no device memory and keeps no state between calls
  *     (the optional kernel-timing recorder at the end of this header aside).
- *   - slkv_score_heads and slkv_compress_layer only enqueue work on `hip_stream` (a
+ *   - slkv_score_heads, slkv_compress_layer and slkv_recompress_layer only enqueue work on `hip_stream` (a
  *     hipStream_t passed as void*, NULL = the default stream) and return without
  *     synchronising.  Host-side descriptors are consumed before the call returns.
  *   - Every argument is validated before the first GPU call; on any error nothing is
