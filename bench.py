@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-recompress", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other budgets of the sweep")
+    ap.add_argument("--other-configs", action="store_true",
+                    help="also time the parity configurations c1, c2 (32 rotating input copies) and c5 (one 1.2 GiB call)")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -209,6 +211,34 @@ def main():
         sweep["avg%d" % avg] = {"ms_per_step": round(ms, 5), "tokens_per_s": round(n / (ms * 1e-3), 1)}
         del cs
     out["budget_sweep"] = sweep
+
+    if args.other_configs:
+        def time_config(lay, bud, copies, reps):
+            cs = [api.LayerCall(lay.dtype, lay.B, lay.Hq, lay.Hkv, lay.d, lay.w, lay.cu_seqlens, bud) for _ in range(copies)]
+            qs = [api.to_device(lay.qwin, lay.dtype) for _ in range(copies)]
+            ks = [api.to_device(lay.k, lay.dtype) for _ in range(copies)]
+            vs = [api.to_device(lay.v, lay.dtype) for _ in range(copies)]
+            for i in range(copies):
+                cs[i].run(qs[i], ks[i], vs[i])
+            torch.cuda.synchronize()
+            a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a_.record()
+            for r in range(reps):
+                cs[r % copies].run(qs[r % copies], ks[r % copies], vs[r % copies])
+            b_.record()
+            torch.cuda.synchronize()
+            ms_ = a_.elapsed_time(b_) / reps
+            toks = int(lay.cu_seqlens[-1])
+            return {"ms_per_call": round(ms_, 5), "tokens_per_s": round(toks / (ms_ * 1e-3), 1), "input_copies": copies}
+        other = {}
+        lay = wl.config1()
+        other["c1"] = time_config(lay, B.slkv_allocate_budgets(lay.meta["inf"], lay.Hkv, lay.meta["avg"], lay.meta["fixed"])[0], 32, 128)
+        lay = wl.config2()
+        other["c2"] = time_config(lay, B.slkv_allocate_budgets(lay.meta["inf"], lay.Hkv, lay.meta["avg"], lay.meta["fixed"])[0], 32, 128)
+        lay = wl.config5()
+        other["c5"] = time_config(lay, B.slkv_allocate_budgets(inf, Hkv, 512, 64)[wl.config5_layer_row(inf)], 1, 10)
+        out["other_configs"] = other
+        del lay
 
     # Decode-time re-compression of a grown ragged cache (c6): 32 sequences x 8 KV heads
     if not args.no_recompress:
