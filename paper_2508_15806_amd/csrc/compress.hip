@@ -54,23 +54,13 @@ union Pack16 {
 };
 
 // Segment of a block / row: the largest s with prefix[s] <= x (prefix non-decreasing, prefix[nseg] > x).
-// Device-resident table: binary search.
-__device__ __forceinline__ int find_segment(const SegTableDev& tab, const int32_t* prefix, int x) {
-  int lo = 0, hi = tab.nseg - 1;
+__device__ __forceinline__ int find_segment(const int32_t* prefix, int nseg, int x) {
+  int lo = 0, hi = nseg - 1;
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
     if (prefix[mid] <= x) lo = mid; else hi = mid - 1;
   }
   return lo;
-}
-// Kernel-argument table: count the entries <= x.  The loads do not depend on one another, so the
-// lookup costs one scalar-load latency at the start of the kernel instead of one per search step
-// (entries past nseg repeat the end value, which is > x).
-__device__ __forceinline__ int find_segment(const SegTable&, const int32_t (&prefix)[kMaxSegPerLaunch + 1], int x) {
-  int s = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxSegPerLaunch; ++i) s += prefix[i] <= x ? 1 : 0;
-  return s;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -121,7 +111,7 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   const int l32 = lane & 31, half = lane >> 5;
 
   const int bid = blockIdx.x;
-  const int seg = find_segment(tab, tab.chunk_begin, bid);
+  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
   const int chunk = bid - tab.chunk_begin[seg];
   const int m = tab.n[seg] - w;
   const int key_begin = chunk * CH;
@@ -387,7 +377,7 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
   const int tid = threadIdx.x;
   const int l32 = tid & (TROWS - 1), sub = tid / TROWS;
   const int bid = blockIdx.x;
-  const int seg = find_segment(tab, tab.chunk_begin, bid);
+  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
   const int chunk = bid - tab.chunk_begin[seg];
   const int m = tab.n[seg] - w;
   const int key_begin = chunk * CH;
@@ -851,7 +841,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const Gather
   const int64_t row0 = tab.out_off[0], row1 = tab.out_off[tab.nseg];
   const int64_t row = row0 + rel;
   if (row >= row1) return;
-  const int seg = find_segment(tab, tab.out_off, (int)row);
+  const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
   if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by select_kernel
   const int64_t tok = (int64_t)tab.tok_begin[seg] + kept_idx[row];
   const int64_t h = tab.head[seg];
