@@ -23,8 +23,8 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/compress_layer_c3_avg256_rocprofv3.md): either scoring pass, 67610 KiB read + 1000 KiB written.
-MEASURED_TRAFFIC_BYTES = 70.3e6
+# (profiles/compress_layer_c3_avg256_rocprofv3.md): either scoring pass, 67600 KiB read + 1000 KiB written.
+MEASURED_TRAFFIC_BYTES = 70.2e6
 
 
 def parse():
