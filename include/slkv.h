@@ -152,6 +152,7 @@ slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes);
  *          m_b entries starting at Hkv*cu[b] + h*n_b and is written only when the segment is
  *          actually ranked (n_b > max(C_h, w) and 0 < k < m_b).
  * out_capacity_rows: rows available in d_k_out / d_v_out / d_kept_idx
+ * d_k, d_v may be NULL when the batch holds no tokens; d_k_out, d_v_out, d_kept_idx when nothing is kept.
  * Errors: NULL, BAD_ARG, UNSUPPORTED, WORKSPACE, CAPACITY, HIP.
  */
 slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin,

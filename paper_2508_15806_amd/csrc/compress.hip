@@ -1055,10 +1055,19 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
                                 const int32_t* d_pos_in, void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
                                 int32_t* d_pos_out, int64_t* d_out_offsets, float* d_importance, float* d_pooled,
                                 int64_t out_capacity_rows, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!d_qwin || !d_k || !d_v || !d_k_out || !d_v_out || !d_kept_idx || !d_workspace)
+  // an input without rows, or an output without kept rows, may come with NULL buffers
+  int64_t rows_in = 0, rows_kept = 0;
+  for (const Seg& sg : g.segs) {
+    rows_in += sg.n;
+    rows_kept += kept_rows(sg.n, g.w, sg.cap);
+  }
+  if (!d_qwin || !d_workspace || (rows_in > 0 && (!d_k || !d_v)) ||
+      (rows_kept > 0 && (!d_k_out || !d_v_out || !d_kept_idx)))
     return fail(SLKV_ERR_NULL, "a required device pointer is NULL");
-  if ((d_pos_in == nullptr) != (d_pos_out == nullptr))
+  if (rows_kept > 0 && (d_pos_in == nullptr) != (d_pos_out == nullptr))
     return fail(SLKV_ERR_NULL, "d_pos_in and d_pos_out must be given together");
+  if (!d_pos_in || !d_pos_out) d_pos_in = nullptr, d_pos_out = nullptr;   // nothing kept: nothing to carry
+
   const void* ptrs[] = {d_qwin, d_k, d_v, d_pos_in, d_k_out, d_v_out, d_kept_idx, d_pos_out, d_out_offsets,
                         d_importance, d_pooled, d_workspace};
   for (const void* ptr : ptrs)

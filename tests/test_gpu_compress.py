@@ -187,3 +187,19 @@ def test_extreme_logits_take_the_running_maximum_path():
     # (its true weight is about e^-100), so only the large keys can be ranked
     rep = check(lay, np.array([w + 50, w + 8], dtype=np.int32))
     assert rep["ranked"] == 4
+
+
+def test_batch_without_tokens():
+    # every sequence empty: the inputs and outputs have no rows (torch hands out NULL pointers for
+    # them); the call still has to succeed and write the offsets
+    import torch
+    from paper_2508_15806_amd import api
+    call = api.LayerCall("bf16", 3, 4, 2, 128, 16, np.zeros(4, dtype=np.int64), np.array([40, 7], dtype=np.int32))
+    assert call.total_kept == 0
+    q = torch.zeros((3, 4, 16, 128), dtype=torch.bfloat16, device="cuda")
+    empty = torch.empty((2, 0, 128), dtype=torch.bfloat16, device="cuda")
+    call.out_offsets.fill_(-1)
+    B.slkv_compress_layer(call.layer, q, empty, empty, empty.reshape(0, 128), empty.reshape(0, 128),
+                          torch.empty((0,), dtype=torch.int32, device="cuda"), call.workspace, call.out_offsets)
+    torch.cuda.synchronize()
+    assert (call.out_offsets.cpu().numpy() == 0).all()

@@ -104,3 +104,16 @@ def test_hundreds_of_segments_use_the_device_resident_table():
     bud = np.array([60, 300, 16, 128], dtype=np.int32)
     rep = check(rc, bud)
     assert rep["segments"] == 300 and rep["ranked"] > 100
+
+
+def test_cache_without_rows():
+    # every segment empty: NULL input buffers (torch's empty tensors) are accepted, offsets are written
+    import torch
+    call = api.RaggedCall("bf16", 2, 4, 2, 128, 16, np.zeros(5, dtype=np.int64), np.array([40, 7], dtype=np.int32))
+    assert call.total_kept == 0
+    q = torch.zeros((2, 4, 16, 128), dtype=torch.bfloat16, device="cuda")
+    empty = torch.empty((0, 128), dtype=torch.bfloat16, device="cuda")
+    call.out_offsets.fill_(-1)
+    call.run(q, empty, empty, torch.empty((0,), dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert (call.out_offsets.cpu().numpy() == 0).all()
