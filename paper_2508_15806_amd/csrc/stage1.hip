@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
     __shared__ float sh_bound[NW];
     __shared__ uint32_t sh_cnt[NW];
     __shared__ float cand_val[kS1Cand];
-    __shared__ int32_t cand_pos[kS1Cand];
+    __shared__ uint64_t cand_key[kS1Cand];   // (order-preserving key of the weight) << 32 | ~position
     const int lane = tid & 63, wv = tid >> 6;
     const int32_t ngroups = n >> 2;      // n % 4 == 0: the row is whole 16-byte groups
 
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
     // of candidates found so far plus the candidates of the same element in lower lanes.
     uint32_t base = 0;                   // wave-uniform
     float* my_val = cand_val + wv * kWaveCand;
-    int32_t* my_pos = cand_pos + wv * kWaveCand;
+    uint64_t* my_key = cand_key + wv * kWaveCand;
 #pragma unroll
     for (int i = 0; i < kS1Resident / 4; ++i) {
       const int32_t g = i * NT + tid;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
           if (is && slot < (uint32_t)kWaveCand) {
             my_val[slot] = x[c];
-            my_pos[slot] = 4 * g + c;
+            my_key[slot] = ((uint64_t)float_key(x[c]) << 32) | (uint32_t)(~(uint32_t)(4 * g + c));
           }
           base += (uint32_t)__popcll(mask);
         }
@@ -151,32 +151,46 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
     }
     if (fits && nc >= (uint32_t)topk) {
       // A candidate belongs to T_k if fewer than K candidates are ahead of it (larger, or equal
-      // at a lower position).  Candidate c (in the order of the parts) is counted by thread c.
-      // Up to 64 candidates, the usual case, are handled by the first wave alone.
-      const bool one_wave = nc <= (uint32_t)kWave;
+      // at a lower position: one comparison of the packed keys).  Up to 256 candidates are handled
+      // by the first wave alone, each lane counting for up to four of them; the other waves retire.
+      constexpr int kPerLane = 4;
+      const bool one_wave = nc <= (uint32_t)(kWave * kPerLane);
       if (one_wave && wv != 0) return;
       double wo = 0.0, wd = 0.0;
-      for (uint32_t c = tid; c < nc; c += NT) {
-        uint32_t part = 0, idx = c;
+      const uint32_t stride = one_wave ? kWave : NT;
+      const uint32_t per_thread = (nc + stride - 1) / stride;    // uniform over the workgroup
+      for (uint32_t c0 = 0; c0 < per_thread; c0 += kPerLane) {
+        uint64_t mine[kPerLane];
+        float xval[kPerLane];
+        uint32_t ahead[kPerLane];
 #pragma unroll
-        for (int i = 0; i < NW - 1; ++i)
-          if (part == (uint32_t)i && idx >= cnt[i]) {
-            idx -= cnt[i];
-            part = i + 1;
-          }
-        const float x = cand_val[part * kWaveCand + idx];
-        const int32_t px = cand_pos[part * kWaveCand + idx];
-        uint32_t ahead = 0;
+        for (int q = 0; q < kPerLane; ++q) {
+          const uint32_t c = (c0 + q) * stride + (one_wave ? lane : tid);
+          uint32_t part = 0, idx = c;
 #pragma unroll
-        for (int q = 0; q < NW; ++q)
-          for (uint32_t o = 0; o < cnt[q]; ++o) {
-            const float y = cand_val[q * kWaveCand + o];
-            const int32_t py = cand_pos[q * kWaveCand + o];
-            ahead += (y > x || (y == x && py < px)) ? 1u : 0u;
-          }
-        if (ahead < (uint32_t)topk) {
-          if (px >= needle_start && px < ne) wo += (double)x; else wd += (double)x;
+          for (int i = 0; i < NW - 1; ++i)
+            if (part == (uint32_t)i && idx >= cnt[i]) {
+              idx -= cnt[i];
+              part = i + 1;
+            }
+          const bool have = c < nc;
+          mine[q] = have ? cand_key[part * kWaveCand + idx] : ~0ull;   // nothing is ahead of the filler, and it is never summed
+          xval[q] = have ? cand_val[part * kWaveCand + idx] : 0.f;
+          ahead[q] = have ? 0u : (uint32_t)topk;
         }
+#pragma unroll
+        for (int p = 0; p < NW; ++p)
+          for (uint32_t o = 0; o < cnt[p]; ++o) {
+            const uint64_t ko = cand_key[p * kWaveCand + o];
+#pragma unroll
+            for (int q = 0; q < kPerLane; ++q) ahead[q] += ko > mine[q] ? 1u : 0u;
+          }
+#pragma unroll
+        for (int q = 0; q < kPerLane; ++q)
+          if (ahead[q] < (uint32_t)topk) {
+            const int32_t px = (int32_t)(~(uint32_t)mine[q]);
+            if (px >= needle_start && px < ne) wo += (double)xval[q]; else wd += (double)xval[q];
+          }
       }
       if (one_wave) {
         wo = wave_sum<double>(wo);
