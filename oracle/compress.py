@@ -103,10 +103,12 @@ def kept_count(n, w, cap):
     return max(cap, w)
 
 
-def compress_segment(q_group, k_seg, v_seg, w, cap, pool_kernel=7, pool_mode=POOL_MAX):
+def compress_segment(q_group, k_seg, v_seg, w, cap, pool_kernel=7, pool_mode=POOL_MAX, scores=None):
     """Algorithm 3 for one sequence and one KV head.
 
     q_group: [G, w, d]; k_seg, v_seg: [n, d]; cap: the head's capacity C.
+    scores: optional (importance, pooled) pair returned by an earlier call on the same
+    inputs and pooling (they do not depend on the capacity); reused instead of recomputed.
     Returns a dict: kept_idx (int64, ascending history then window), k_out,
     v_out (bit copies), importance, pooled (None on the early-out path), tau, k.
     """
@@ -117,19 +119,25 @@ def compress_segment(q_group, k_seg, v_seg, w, cap, pool_kernel=7, pool_mode=POO
                     importance=None, pooled=None, tau=None, k=None)
     m = n - w                                      # history / window split
     k_keep = min(max(cap - w, 0), m)               # C_H = C - window, clamped
-    imp = window_importance(q_group, k_seg[:m])
-    pooled = pool_1d(imp, pool_kernel, pool_mode)
+    if scores is None:
+        imp = window_importance(q_group, k_seg[:m])
+        pooled = pool_1d(imp, pool_kernel, pool_mode)
+    else:
+        imp, pooled = scores
     hist_idx, tau = select_topk(pooled, k_keep)
     idx = np.concatenate([hist_idx, np.arange(m, n, dtype=np.int64)])
     return dict(kept_idx=idx, k_out=k_seg[idx].copy(), v_out=v_seg[idx].copy(),
                 importance=imp, pooled=pooled, tau=tau, k=k_keep)
 
 
-def compress_layer(qwin, k, v, cu_seqlens, budgets, w, pool_kernel=7, pool_mode=POOL_MAX):
+def compress_layer(qwin, k, v, cu_seqlens, budgets, w, pool_kernel=7, pool_mode=POOL_MAX, score_cache=None):
     """One layer over a ragged batch.
 
     qwin: [B, Hq, w, d]; k, v: [Hkv, T, d] with sequences packed along T at
     cu_seqlens[B+1]; budgets: [Hkv] capacities of this layer.
+    score_cache: optional dict that keeps (importance, pooled) per (b, h) between calls on the
+    same inputs and pooling with other budgets (memoisation only: the scores do not depend on
+    the capacities).
     Returns dict: segments (list over b*Hkv+h of compress_segment results),
     out_offsets (int64 [B*Hkv+1]), k_out, v_out ([total_kept, d] packed).
     """
@@ -142,8 +150,11 @@ def compress_layer(qwin, k, v, cu_seqlens, budgets, w, pool_kernel=7, pool_mode=
     for b in range(B):
         t0, t1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
         for h in range(Hkv):
+            cached = score_cache.get((b, h)) if score_cache is not None else None
             r = compress_segment(qwin[b, h * G:(h + 1) * G], k[h, t0:t1], v[h, t0:t1],
-                                 w, int(budgets[h]), pool_kernel, pool_mode)
+                                 w, int(budgets[h]), pool_kernel, pool_mode, scores=cached)
+            if score_cache is not None and r["importance"] is not None:
+                score_cache[(b, h)] = (r["importance"], r["pooled"])
             segs.append(r)
             offs.append(offs[-1] + r["kept_idx"].shape[0])
     k_out = np.concatenate([s["k_out"] for s in segs], axis=0)

@@ -228,3 +228,17 @@ def test_ragged_batch_uses_own_tokens():
     res = oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, [20, 20], lay.w, 1)
     ref = brute_importance(lay.qwin[1, 0:2], lay.k[0, 50:50 + 37])
     np.testing.assert_allclose(res["segments"][2]["importance"], ref, rtol=1e-11)
+
+
+def test_score_cache_is_memoisation_only():
+    # the cached scores of one budget row reused under other budgets give what a fresh call gives
+    lay = wl.make_layer((8, 1), [400, 120], 8, 2, 64, 16, dtype="bf16", bias_frac=0.05)
+    cache = {}
+    for bud in ([300, 40], [60, 17], [30, 399], [1000, 5]):
+        a = oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, bud, lay.w, 5, oc.POOL_MAX, score_cache=cache)
+        b = oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, bud, lay.w, 5, oc.POOL_MAX)
+        assert np.array_equal(a["out_offsets"], b["out_offsets"])
+        assert np.array_equal(a["k_out"], b["k_out"]) and np.array_equal(a["v_out"], b["v_out"])
+        for sa, sb in zip(a["segments"], b["segments"]):
+            assert np.array_equal(sa["kept_idx"], sb["kept_idx"]) and sa["tau"] == sb["tau"]
+    assert set(cache) == {(0, 0), (0, 1), (1, 0), (1, 1)}
