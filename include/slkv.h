@@ -162,6 +162,25 @@ slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin,
                                 int64_t out_capacity_rows,
                                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* slkv_compress_layer for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as slkv_compress_layer without the workspace: the scratch
+ * (chunk statistics, log-sum-exp, importance, pooled scores, segment table) lives in a buffer of
+ * SLKV_STATIC_SCRATCH_BYTES that is part of the library's code object, one copy per GPU, held
+ * until the process ends.  A call whose slkv_workspace_bytes() exceeds that size returns
+ * SLKV_ERR_WORKSPACE and enqueues nothing.  The call allocates nothing (no hipMalloc / hipFree).
+ * All calls on one GPU share the buffer: calls that may overlap on one GPU (different streams
+ * without ordering between them, or several host threads) race and must be serialised by the
+ * caller.  The buffer's address is looked up on the first call on each device; make that call
+ * outside stream capture.
+ */
+#define SLKV_STATIC_SCRATCH_BYTES (8u << 20)
+slkv_status slkv_compress_layer_static(const slkv_layer_desc* desc, const void* d_qwin,
+                                       const void* d_k, const void* d_v,
+                                       void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                       int64_t* d_out_offsets, float* d_importance, float* d_pooled,
+                                       int64_t out_capacity_rows, void* hip_stream);
+
 /* ------------------------------------------------------------------ Stage 2b on a ragged cache
  * Section 3.4 runs the selection whenever a head's cache length exceeds its capacity, which
  * also happens during generation, when the cache is the compacted output of an earlier call

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SLKV_OK", 1: "SLKV_ERR_NULL", 2: "SLKV_ERR_BAD_ARG", 3: "SLK
 
 EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads",
            "slkv_score_heads_workspace_bytes", "slkv_allocate_budgets", "slkv_fixed_from_beta",
-           "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer",
+           "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer", "slkv_compress_layer_static",
            "slkv_recompress_sizes", "slkv_recompress_workspace_bytes", "slkv_recompress_layer",
            "slkv_profile_begin", "slkv_profile_end"]
 
@@ -85,6 +85,8 @@ def lib():
         L.slkv_compress_layer.restype = C.c_int
         L.slkv_compress_layer.argtypes = [C.POINTER(LayerDesc)] + [C.c_void_p] * 9 + [C.c_int64, C.c_void_p,
                                                                                       C.c_size_t, C.c_void_p]
+        L.slkv_compress_layer_static.restype = C.c_int
+        L.slkv_compress_layer_static.argtypes = [C.POINTER(LayerDesc)] + [C.c_void_p] * 9 + [C.c_int64, C.c_void_p]
         L.slkv_recompress_sizes.restype = C.c_int
         L.slkv_recompress_sizes.argtypes = [C.POINTER(RaggedDesc), C.c_void_p, C.c_void_p]
         L.slkv_recompress_workspace_bytes.restype = C.c_int
@@ -173,6 +175,14 @@ def slkv_compress_layer(layer, qwin, k, v, k_out, v_out, kept_idx, workspace, ou
                                      _ptr(kept_idx), _ptr(out_offsets), _ptr(importance), _ptr(pooled),
                                      int(k_out.shape[0]), _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                      _stream(stream)))
+
+
+def slkv_compress_layer_static(layer, qwin, k, v, k_out, v_out, kept_idx, out_offsets=None,
+                               importance=None, pooled=None, stream=None):
+    """As slkv_compress_layer, with the library's own static scratch buffer instead of a workspace."""
+    _check(lib().slkv_compress_layer_static(C.byref(layer.desc), _ptr(qwin), _ptr(k), _ptr(v), _ptr(k_out), _ptr(v_out),
+                                            _ptr(kept_idx), _ptr(out_offsets), _ptr(importance), _ptr(pooled),
+                                            int(k_out.shape[0]), _stream(stream)))
 
 
 class Ragged:

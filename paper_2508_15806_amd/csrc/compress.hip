@@ -12,6 +12,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -1219,6 +1220,29 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
 
 using namespace slkv;
 
+// Scratch of slkv_compress_layer_static: one copy per GPU, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[SLKV_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device (looked up once per device).
+static slkv_status static_scratch(void** out) {
+  constexpr int kMaxDev = 64;
+  static std::mutex mu;
+  static void* ptrs[kMaxDev] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(SLKV_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDev) return fail(SLKV_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, kMaxDev - 1);
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptrs[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(SLKV_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    ptrs[dev] = ptr;
+  }
+  *out = ptrs[dev];
+  return SLKV_OK;
+}
+
 extern "C" slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes) {
   clear_error();
   if (!bytes) return fail(SLKV_ERR_NULL, "bytes is NULL");
@@ -1244,6 +1268,27 @@ extern "C" slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const vo
   layer_geometry(desc, g);
   return run_geometry(g, d_qwin, d_k, d_v, nullptr, d_k_out, d_v_out, d_kept_idx, nullptr, d_out_offsets, d_importance,
                       d_pooled, out_capacity_rows, d_workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" slkv_status slkv_compress_layer_static(const slkv_layer_desc* desc, const void* d_qwin, const void* d_k,
+                                                  const void* d_v, void* d_k_out, void* d_v_out, int32_t* d_kept_idx,
+                                                  int64_t* d_out_offsets, float* d_importance, float* d_pooled,
+                                                  int64_t out_capacity_rows, void* hip_stream) {
+  clear_error();
+  slkv_status vs = validate_desc(desc);
+  if (vs != SLKV_OK) return vs;
+  Geometry g;
+  layer_geometry(desc, g);
+  Plan p;
+  make_plan(g, p);
+  if (p.total_bytes > (size_t)SLKV_STATIC_SCRATCH_BYTES)
+    return fail(SLKV_ERR_WORKSPACE, "this call needs %zu bytes of scratch, the static buffer holds %zu: use slkv_compress_layer",
+                p.total_bytes, (size_t)SLKV_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  vs = static_scratch(&ws);
+  if (vs != SLKV_OK) return vs;
+  return run_geometry(g, d_qwin, d_k, d_v, nullptr, d_k_out, d_v_out, d_kept_idx, nullptr, d_out_offsets, d_importance,
+                      d_pooled, out_capacity_rows, ws, (size_t)SLKV_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 extern "C" slkv_status slkv_recompress_workspace_bytes(const slkv_ragged_desc* desc, size_t* bytes) {
