@@ -26,11 +26,13 @@ class LayerCall:
     """Device buffers + descriptor for repeated calls on one layer's shapes."""
 
     def __init__(self, dtype, B_, Hq, Hkv, d, w, cu_seqlens, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX,
-                 device="cuda", debug_scores=False):
+                 device="cuda", debug_scores=False, k_strides=None, v_strides=None):
+        """k_strides / v_strides: (token stride, head stride) in elements; default = head-major
+        contiguous [Hkv][T][d]."""
         T = int(cu_seqlens[-1])
         self.dtype = dtype
         self.layer = B.Layer(B.SLKV_BF16 if dtype == "bf16" else B.SLKV_F32, B_, Hq, Hkv, d, w, cu_seqlens,
-                             budgets, (d, T * d), (d, T * d), pool_kernel, pool)
+                             budgets, k_strides or (d, T * d), v_strides or (d, T * d), pool_kernel, pool)
         self.offsets, self.total_kept = B.slkv_compacted_sizes(self.layer)
         tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
         rows = max(self.total_kept, 1)

@@ -68,6 +68,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libslkv.so is missing: build it with `python -m paper_2508_15806_amd.build` "
                                "(there is no CPU fallback)")
+        # torch owns device memory and streams, so its HIP runtime has to be the one this process
+        # uses: load it before the library (loaded the other way round, the library would pull in
+        # the system runtime first and the two would not see each other's devices and streams)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.slkv_status_str.restype = C.c_char_p
         L.slkv_status_str.argtypes = [C.c_int]

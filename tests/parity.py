@@ -41,14 +41,25 @@ class Guarded:
             assert (host[BAND + nbytes:] == SENTINEL).all(), "write past the end of %s" % name
 
 
-def run_gpu(lay, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX):
+def run_gpu(lay, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX, token_major=False):
+    """token_major: K is uploaded as [T][Hkv][d] and V as [T][Hkv][d + 24] (padded rows, so V's
+    strides differ from K's) instead of head-major contiguous [Hkv][T][d]."""
     import torch
+    ks = vs = None
+    k_host, v_host = lay.k, lay.v
+    if token_major:
+        pad = 24
+        ks = (lay.Hkv * lay.d, lay.d)
+        vs = (lay.Hkv * (lay.d + pad), lay.d + pad)
+        k_host = np.ascontiguousarray(np.transpose(lay.k, (1, 0, 2)))
+        v_host = np.full((lay.v.shape[1], lay.Hkv, lay.d + pad), 0x7F7F if lay.dtype == "bf16" else 1e30, dtype=lay.v.dtype)
+        v_host[:, :, :lay.d] = np.transpose(lay.v, (1, 0, 2))
     call = api.LayerCall(lay.dtype, lay.B, lay.Hq, lay.Hkv, lay.d, lay.w, lay.cu_seqlens, budgets,
-                         pool_kernel, pool, debug_scores=True)
+                         pool_kernel, pool, debug_scores=True, k_strides=ks, v_strides=vs)
     guard = Guarded(call)
     q = api.to_device(lay.qwin, lay.dtype)
-    k = api.to_device(lay.k, lay.dtype)
-    v = api.to_device(lay.v, lay.dtype)
+    k = api.to_device(k_host, lay.dtype)
+    v = api.to_device(v_host, lay.dtype)
     call.run(q, k, v)
     torch.cuda.synchronize()
     guard.check()
