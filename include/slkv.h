@@ -140,7 +140,14 @@ typedef struct {
  * the kept counts in segment order s = b*Hkv + h; *total_kept (may be NULL) their sum. */
 slkv_status slkv_compacted_sizes(const slkv_layer_desc* desc, int64_t* h_out_offsets,
                                  int64_t* total_kept);
-/* Device workspace slkv_compress_layer needs for this descriptor. */
+/* Device workspace slkv_compress_layer needs for this descriptor.
+ * A workspace has to be ZERO-FILLED ONCE by the caller before the first call that uses it (its
+ * first SLKV_WORKSPACE_HEADER_BYTES hold counters with which the workgroups of a kernel find
+ * out which of them finishes a segment last); every call leaves them zero again, so the same
+ * workspace serves any number of later calls, of any descriptor it is large enough for, also
+ * from a replayed HIP graph.  Its other contents are scratch.  Two calls that may overlap in
+ * time need a workspace each. */
+#define SLKV_WORKSPACE_HEADER_BYTES 65536
 slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes);
 
 /* d_qwin   [B][Hq][w][d] window queries (device, read only)
@@ -165,7 +172,7 @@ slkv_status slkv_compress_layer(const slkv_layer_desc* desc, const void* d_qwin,
 /* slkv_compress_layer for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, results and errors as slkv_compress_layer without the workspace: the scratch
- * (chunk statistics, log-sum-exp, importance, pooled scores, segment table) lives in a buffer of
+ * (chunk statistics, log-sum-exp, importance, pooled scores, block histograms, segment table) lives in a buffer of
  * SLKV_STATIC_SCRATCH_BYTES that is part of the library's code object, one copy per GPU, held
  * until the process ends.  A call whose slkv_workspace_bytes() exceeds that size returns
  * SLKV_ERR_WORKSPACE and enqueues nothing.  The call allocates nothing (no hipMalloc / hipFree).
@@ -204,7 +211,8 @@ typedef struct {
 /* Kept-row counts of slkv_recompress_layer (same outputs as slkv_compacted_sizes). */
 slkv_status slkv_recompress_sizes(const slkv_ragged_desc* desc, int64_t* h_out_offsets,
                                   int64_t* total_kept);
-/* Device workspace slkv_recompress_layer needs for this descriptor. */
+/* Device workspace slkv_recompress_layer needs for this descriptor (zero-filled once before its
+ * first use, like the workspace of slkv_compress_layer). */
 slkv_status slkv_recompress_workspace_bytes(const slkv_ragged_desc* desc, size_t* bytes);
 
 /* d_qwin   [B][Hq][w][d] queries of the latest w tokens (device, read only)
@@ -235,7 +243,7 @@ slkv_status slkv_recompress_layer(const slkv_ragged_desc* desc, const void* d_qw
  */
 typedef enum {
   SLKV_K_SCORE_STATS = 0,   /* logits + per-row sum-exp of every key chunk */
-  SLKV_K_COMBINE = 1,       /* per-row log-sum-exp over the key chunks */
+  SLKV_K_COMBINE = 1,       /* not launched any more: the statistics pass folds the chunks itself */
   SLKV_K_SCORE_ACCUM = 2,   /* logits + exp(logit - lse) summed down the rows */
   SLKV_K_SELECT = 3,        /* pooling + top-k */
   SLKV_K_GATHER = 4,        /* K/V row gather */

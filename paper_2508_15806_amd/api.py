@@ -40,7 +40,7 @@ class LayerCall:
         self.v_out = torch.empty((rows, d), dtype=tdt, device=device)
         self.kept_idx = torch.empty((rows,), dtype=torch.int32, device=device)
         self.out_offsets = torch.empty((B_ * Hkv + 1,), dtype=torch.int64, device=device)
-        self.workspace = torch.empty((B.slkv_workspace_bytes(self.layer),), dtype=torch.uint8, device=device)
+        self.workspace = torch.zeros((B.slkv_workspace_bytes(self.layer),), dtype=torch.uint8, device=device)   # zero-filled once
         self.importance = self.pooled = None
         if debug_scores:
             self.importance = torch.zeros((max(Hkv * T, 1),), dtype=torch.float32, device=device)
@@ -67,7 +67,7 @@ class RaggedCall:
         self.kept_idx = torch.empty((rows,), dtype=torch.int32, device=device)
         self.pos_out = torch.empty((rows,), dtype=torch.int32, device=device) if positions else None
         self.out_offsets = torch.empty((B_ * Hkv + 1,), dtype=torch.int64, device=device)
-        self.workspace = torch.empty((B.slkv_recompress_workspace_bytes(self.rag),), dtype=torch.uint8, device=device)
+        self.workspace = torch.zeros((B.slkv_recompress_workspace_bytes(self.rag),), dtype=torch.uint8, device=device)
         self.importance = self.pooled = None
         if debug_scores:
             self.importance = torch.zeros((max(rows_in, 1),), dtype=torch.float32, device=device)

@@ -1,6 +1,6 @@
 // Stage 2b of SurfaceLogicKV (Section 3.4, Eq. 7-8, Algorithm 3) on gfx950:
-//   pass 1  score_*<.., 1>  window-query x history-key logits, per-row (reference, sum-exp) per key chunk
-//   combine                  per-row log-sum-exp over the key chunks
+//   pass 1  score_*<.., 1>  window-query x history-key logits, per-row log-sum-exp of every key chunk;
+//                            the chunk of a segment that finishes last folds them into the row's log-sum-exp
 //   pass 2  score_*<.., 2>  logits again, exp(logit - lse) summed down the G*w rows -> importance
 //   select                   1-D pooling + per-head top-k (radix select, ordered compaction)
 //   gather                   kept K/V rows -> compacted ragged cache
@@ -9,8 +9,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <type_traits>
@@ -18,6 +18,17 @@
 
 #include "device_utils.h"
 #include "slkv_internal.h"
+
+// Development aid, compiled only with -DSLKV_TRACE: clock stamps of chosen workgroups.
+#ifdef SLKV_TRACE
+__device__ long long slkv_trace_buf[64 * 1024];
+#define SLKV_STAMP(wg, slot) do { if (threadIdx.x == 0 && (wg) < 1024) slkv_trace_buf[(wg) * 16 + (slot)] = wall_clock64(); } while (0)
+extern "C" int slkv_trace_read(long long* h, int n) {
+  return (int)hipMemcpyFromSymbol(h, HIP_SYMBOL(slkv_trace_buf), (size_t)n * sizeof(long long));
+}
+#else
+#define SLKV_STAMP(wg, slot) do {} while (0)
+#endif
 
 namespace slkv {
 
@@ -34,15 +45,24 @@ struct SegTable {
   int32_t score_off[kMaxSegPerLaunch];   // offset of the segment in the importance / pooled arrays
   int32_t chunk_begin[kMaxSegPerLaunch + 1];  // prefix of key-chunk counts (0 chunks when not ranked)
   int32_t seg_global[kMaxSegPerLaunch];  // index b*Hkv + h
+  int32_t blk_begin[kMaxSegPerLaunch + 1];    // prefix of selection-block counts (one block when not ranked)
+  int32_t hblk[kMaxSegPerLaunch];        // first block histogram of the segment (segments of several blocks)
+  int32_t tick[kMaxSegPerLaunch];        // ticket slot of the segment (segments of several chunks or blocks)
 };
 
 // The same table in device memory, for calls with more segments than fit a kernel argument.
-// chunk_begin and out_off are prefixes over all segments of the call.
+// chunk_begin, blk_begin and out_off are prefixes over all segments of the call.
 struct SegTableDev {
   int32_t nseg;
   int32_t total_chunks;
-  int32_t *tok_begin, *n, *kkeep, *out_off, *head, *qrow_off, *score_off, *chunk_begin, *seg_global;
+  int32_t *tok_begin, *n, *kkeep, *out_off, *head, *qrow_off, *score_off, *chunk_begin, *seg_global, *blk_begin, *hblk, *tick;
 };
+
+// The workspace starts with ticket words (zero between calls): slot t counts the key chunks of a
+// segment that have finished the statistics pass, slot kTicketSelect + t its selection blocks.
+constexpr int kTicketSlots = 8192;
+constexpr int kTicketSelect = kTicketSlots;
+constexpr size_t kTicketBytes = 2 * (size_t)kTicketSlots * sizeof(uint32_t);
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
@@ -74,6 +94,81 @@ __device__ __forceinline__ void merge_stats(float& m, float& s, float m2, float 
   m = mn;
 }
 
+// Data that one workgroup writes and another workgroup of the SAME kernel reads (after a ticket
+// tells it that the writers are done) moves with device-scope accesses: the stores are written
+// through to memory and the loads do not take a line that another XCD's L2 may hold newer, so no
+// L2 write-back / invalidate (a device-scope fence costs tens of microseconds per kernel here) is
+// needed.  The writer waits for its stores (workgroup release fence + barrier) before one thread
+// takes the ticket.
+__device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev(uint32_t* p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t ld_dev(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Takes a ticket of `count` arrivals after the workgroup's device-scope stores have completed.
+// Returns true in the workgroup that arrives last (its ticket word is zero again afterwards).
+// `flag` is one word of LDS.  Every thread of the workgroup must call it.
+__device__ __forceinline__ bool last_arrival(uint32_t* ticket, uint32_t count, uint32_t* flag) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores above have been performed
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == count - 1u) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *flag = old;
+  }
+  __syncthreads();
+  const bool last = *flag == count - 1u;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  return last;
+}
+
+// Per-row log-sum-exp (log2 domain) of a segment from the log-sum-exp of its key chunks
+// (part[chunk][row]; -inf for a chunk without keys for the row), one thread per row.  The loads
+// of a batch are all in flight together and the exponentials are independent of each other;
+// only the additions run in chunk order, so the result does not depend on timing.
+__device__ __forceinline__ void segment_lse(int c0, int c1, int seg, int Rpad, const float* __restrict__ part,
+                                            float* __restrict__ lse) {
+  constexpr int NB = 32;
+  for (int row = threadIdx.x; row < Rpad; row += blockDim.x) {
+    float mm = -INFINITY, ss = 0.f;
+    for (int c = c0; c < c1; c += NB) {
+      float v[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) v[u] = c + u < c1 ? ld_dev(part + (int64_t)(c + u) * Rpad + row) : -INFINITY;
+      float bm = v[0];
+#pragma unroll
+      for (int u = 1; u < NB; ++u) bm = fmaxf(bm, v[u]);
+      const float mn = fmaxf(mm, bm);
+      const float mu = mn == -INFINITY ? 0.f : mn;
+      float e[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) e[u] = fast_exp2(v[u] - mu);
+      ss *= fast_exp2(mm - mu);
+#pragma unroll
+      for (int u = 0; u < NB; ++u) ss += e[u];
+      mm = mn;
+    }
+    lse[seg * Rpad + row] = ss > 0.f ? mm + log2f(ss) : INFINITY;
+  }
+}
+
+// End of the statistics pass of one key chunk (its pairs are written): the chunk that arrives
+// last at the segment's ticket folds all chunks into the segment's log-sum-exp and clears the
+// ticket for the next call.  `flag` is one word of LDS.
+template <class TAB>
+__device__ __forceinline__ void finish_stats_chunk(const TAB& tab, int seg, int Rpad, const float* __restrict__ part,
+                                                   float* __restrict__ lse, uint32_t* __restrict__ tickets, uint32_t* flag) {
+  const int c0 = tab.chunk_begin[seg], c1 = tab.chunk_begin[seg + 1];
+  if (c1 - c0 > 1) {
+    if (!last_arrival(tickets + tab.tick[seg], (uint32_t)(c1 - c0), flag)) return;
+    SLKV_STAMP(256 + blockIdx.x, 3);
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+  }
+  segment_lse(c0, c1, seg, Rpad, part, lse);
+}
+
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA scoring.  One workgroup (4 waves) owns one chunk of history keys of one segment.
 // K is staged in LDS in tiles of 64 keys (two buffers); up to kPrefetch further tiles are in
@@ -93,7 +188,8 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
                                                          const uint16_t* __restrict__ kmat, int64_t k_stride_tok,
                                                          int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                          float c_log2, float* __restrict__ part,
-                                                         const float* __restrict__ lse, float* __restrict__ imp) {
+                                                         const float* __restrict__ lse, float* __restrict__ imp,
+                                                         float* __restrict__ lse_out, uint32_t* __restrict__ tickets) {
   constexpr int KS = 4 / RB;               // waves along the keys
   constexpr int TK = kTileKeys;
   constexpr int NSUB = TK / 32 / KS;       // 32-key sub-tiles per wave per tile
@@ -106,12 +202,14 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   __shared__ __attribute__((aligned(16))) unsigned char ktile[2][TK * ROWB];
   __shared__ float red[2][RB][TK];
   __shared__ float2 comb[KS][RB * 32 * MT];
+  __shared__ uint32_t sh_flag;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int rb = wv % RB, ks = wv / RB;
   const int l32 = lane & 31, half = lane >> 5;
 
   const int bid = blockIdx.x;
+  if (PASS == 1) SLKV_STAMP(256 + bid, 0);
   const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
   const int chunk = bid - tab.chunk_begin[seg];
   const int m = tab.n[seg] - w;
@@ -306,6 +404,7 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
     do_tile(ntiles - 1, pf1, T{}, F{}, F{});
   }
 
+  if (PASS == 1) SLKV_STAMP(256 + bid, 1);
   if (PASS == 1) {
     // A sum that left the fp32 range (logits far above the chunk's first ones): the whole
     // workgroup repeats the chunk with the running maximum.  Not taken for ordinary inputs.
@@ -353,11 +452,12 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
       float mm = comb[0][row].x, ss = comb[0][row].y;
 #pragma unroll
       for (int k2 = 1; k2 < KS; ++k2) merge_stats(mm, ss, comb[k2][row].x, comb[k2][row].y);
-      if (row < Rpad) {
-        part[((int64_t)bid * Rpad + row) * 2 + 0] = mm;
-        part[((int64_t)bid * Rpad + row) * 2 + 1] = ss;
-      }
+      // the chunk's log-sum-exp of the row (-inf: no key)
+      if (row < Rpad) st_dev(part + (int64_t)bid * Rpad + row, ss > 0.f ? mm + __builtin_amdgcn_logf(ss) : -INFINITY);
     }
+    SLKV_STAMP(256 + bid, 2);
+    finish_stats_chunk(tab, seg, Rpad, part, lse_out, tickets, &sh_flag);
+    SLKV_STAMP(256 + bid, 4);
   }
 }
 
@@ -369,12 +469,14 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
                                                         const float* __restrict__ kmat, int64_t k_stride_tok,
                                                         int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                         float c_log2, float* __restrict__ part,
-                                                        const float* __restrict__ lse, float* __restrict__ imp) {
+                                                        const float* __restrict__ lse, float* __restrict__ imp,
+                                                        float* __restrict__ lse_out, uint32_t* __restrict__ tickets) {
   constexpr int TROWS = 32;                 // keys (pass 1) or query rows (pass 2) per LDS tile
   constexpr int NSUB = 256 / TROWS;         // thread = (lane32, sub): 32 rows x 8 key subsets, or 32 keys x 8 row subsets
   __shared__ __attribute__((aligned(16))) float tile[TROWS][DK];
   __shared__ float lse_s[TROWS];
   __shared__ float2 red[NSUB][TROWS];
+  __shared__ uint32_t sh_flag;
   const int tid = threadIdx.x;
   const int l32 = tid & (TROWS - 1), sub = tid / TROWS;
   const int bid = blockIdx.x;
@@ -426,10 +528,10 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
       if (sub == 0) {
 #pragma unroll
         for (int k2 = 1; k2 < NSUB; ++k2) merge_stats(mm, ss, red[k2][l32].x, red[k2][l32].y);
-        part[((int64_t)bid * Rpad + row) * 2 + 0] = row < R ? mm : -INFINITY;
-        part[((int64_t)bid * Rpad + row) * 2 + 1] = row < R ? ss : 0.f;
+        st_dev(part + (int64_t)bid * Rpad + row, (row < R && ss > 0.f) ? mm + __builtin_amdgcn_logf(ss) : -INFINITY);
       }
     }
+    finish_stats_chunk(tab, seg, Rpad, part, lse_out, tickets, &sh_flag);
   } else {
     // 32 keys at a time; the thread's row subset is rows sub, sub + 8, ... of every query tile
     for (int k0 = key_begin; k0 < key_end; k0 += TROWS) {
@@ -467,43 +569,22 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
   }
 }
 
-// Per-row log-sum-exp (log2 domain) over a segment's chunks.  Block = 16 rows x 16 lanes; lane c
-// folds chunks c, c+16, ... in order, then the 16 partial results are merged by a butterfly.
-template <class TAB>
-__global__ __launch_bounds__(256) void combine_kernel(const TAB tab, int Rpad, const float* __restrict__ part,
-                                                      float* __restrict__ lse) {
-  const int seg = blockIdx.x;
-  const int c0 = tab.chunk_begin[seg], c1 = tab.chunk_begin[seg + 1];
-  if (c0 == c1) return;
-  const int row = blockIdx.y * 16 + (threadIdx.x >> 4);
-  const int cl = threadIdx.x & 15;
-  float mm = -INFINITY, ss = 0.f;
-  if (row < Rpad) {
-    for (int c = c0 + cl; c < c1; c += 16) {
-      const float2 ps = *reinterpret_cast<const float2*>(part + ((int64_t)c * Rpad + row) * 2);
-      merge_stats(mm, ss, ps.x, ps.y);
-    }
-  }
-#pragma unroll
-  for (int dlt = 8; dlt > 0; dlt >>= 1) {
-    const float m2 = __shfl_xor(mm, dlt, 64), s2 = __shfl_xor(ss, dlt, 64);
-    merge_stats(mm, ss, m2, s2);
-  }
-  if (row < Rpad && cl == 0) lse[seg * Rpad + row] = ss > 0.f ? mm + log2f(ss) : INFINITY;
-}
-
 // ------------------------------------------------------------------------------------------
-// Pooling + top-k of one segment per workgroup (Algorithm 3, steps 7-8).  Writes the kept
-// positions: history positions ascending, then the window.
+// Pooling + top-k (Algorithm 3, steps 7-8).  Writes the kept positions: history positions
+// ascending, then the window.
 //
-// The history is processed in rounds of 32768 positions; thread t owns 32 consecutive
-// positions of a round (values reach it through an LDS transposition of coalesced loads), so
-// pooling is a sliding window in registers, equal neighbours share one histogram update and
-// the ordered compaction needs one block scan per round.  A history of one round stays in
-// registers from the first load to the last store.
-// The k-th largest pooled score is found by a radix select whose digits are taken relative to
-// the segment's own [min, max] of score bit patterns (scores are >= 0, so the bit pattern is
-// monotone): 11 bits per level over the remaining range, at most three levels.
+// A segment's history is cut into blocks of kSelBlock positions, one 1024-thread workgroup each.
+//   Phase A (every block): pool the block's importance scores (halo from the neighbours), write
+//     the pooled scores, histogram their leading 11 key bits, publish the histogram.
+//   Phase B (the block of a segment that arrives last at the segment's ticket; a one-block
+//     segment goes straight on): add the block histograms, pick the digit that holds the k-th
+//     largest score, collect that digit's scores in LDS and narrow them down to the exact k-th
+//     largest value tau and the number of scores equal to tau that belong to the top k (ties go
+//     to lower positions); then one ordered compaction of the positions with score > tau, or
+//     == tau among the first `need_eq`.
+// Keys are the bit patterns of the pooled scores (>= 0, so monotone).  In phase B a wave owns 2048
+// consecutive positions of a round of 32768, lane l the positions 64*j + l (j < 32): ballots are in
+// position order, so the ordered compaction needs no scan beyond the 16 wave totals.
 constexpr int kInlineGatherRows = 256;    // segments up to this many kept rows are gathered by select_kernel
 
 struct GatherArgs {
@@ -518,24 +599,366 @@ struct GatherArgs {
 };
 
 constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelBlock = 4096;           // history positions per phase-A block
 constexpr int kSelEPT = 32;
 constexpr int kSelRound = kSelThreads * kSelEPT;
 constexpr int kSelHaloMax = kMaxPool / 2;
-constexpr int kSelStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * kSelHaloMax) >> 5) + 8;
-constexpr int kSelRankMax = 256;       // lists up to this length are ranked by direct counting
-constexpr int kSelCandidates = 3072;   // scores of one first-level digit that the LDS list can hold
+constexpr int kSelRankMax = 256;          // lists up to this length are ranked by direct counting
+constexpr int kSelCandidates = 12288;     // scores of one first-level digit that the LDS list can hold
+constexpr int kDigitShift = 20;           // first-level digit = key >> 20: sign (0), 8 exponent and 3 mantissa bits
+constexpr uint32_t kKeyNone = 0xffffffffu;
+static_assert(kSelBlock + 2 * kSelHaloMax <= kSelCandidates, "the importance staging of phase A lives in the candidate list");
+static_assert(kTicketBytes == SLKV_WORKSPACE_HEADER_BYTES, "the header documents the size of the ticket area");
+static_assert((0x7f800000u >> kDigitShift) < (uint32_t)kHistBins, "every key has a first-level digit inside the histogram");
+
+// Key of a pooled score: its bit pattern; anything that is not a non-negative number (cannot
+// come out of finite inputs) ranks as +infinity, so that both phases count it the same way.
+__device__ __forceinline__ uint32_t score_key(float v) {
+  const uint32_t u = __float_as_uint(v);
+  return u > 0x7f800000u ? 0x7f800000u : u;
+}
+
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+template <int RADIUS, class TAB>   // pooling radius known at compile time (0..3), or -1: any radius
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
+                                                             const float* __restrict__ imp, float* __restrict__ pooled,
+                                                             uint32_t* __restrict__ blockhist, uint32_t* __restrict__ tickets,
+                                                             int32_t* __restrict__ kept_idx, int64_t* __restrict__ d_out_offsets,
+                                                             const GatherArgs ga) {
+  constexpr int NT = kSelThreads, NW = kSelWaves, EPT = kSelEPT, ROUND = kSelRound;
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t cand[kSelCandidates];
+  __shared__ uint32_t small_list[kSelRankMax];
+  __shared__ int32_t sh_pos[kInlineGatherRows];
+  __shared__ uint32_t sh_scan[NW];
+  __shared__ uint32_t sh_wg[NW], sh_we[NW];
+  __shared__ uint32_t res[4];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int bid = blockIdx.x;
+  const int seg = find_segment(tab.blk_begin, tab.nseg, bid);
+  const int blk = bid - tab.blk_begin[seg];
+  const int nblk = tab.blk_begin[seg + 1] - tab.blk_begin[seg];
+  const int n = tab.n[seg];
+  const int kk = tab.kkeep[seg];
+  const int m = n - w;
+  const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
+  const bool small_seg = kept <= kInlineGatherRows;
+  int32_t* out = kept_idx + tab.out_off[seg];
+  if (d_out_offsets && blk == 0 && tid == 0) {
+    d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
+    if (seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
+  }
+  auto emit = [&](int pos, int j) __attribute__((always_inline)) {   // kept position j goes to output slot pos
+    if ((uint32_t)pos < (uint32_t)kept) {
+      out[pos] = j;
+      if (small_seg) sh_pos[pos] = j;
+    }
+  };
+  SLKV_STAMP(bid, 0);
+  if (small_seg)
+    for (int i = tid; i < kInlineGatherRows; i += NT) sh_pos[i] = 0;
+  __syncthreads();
+  const bool ranked = kk > 0 && kk < m;
+  if (!ranked) {
+    // one block: the whole segment, or only its window (plus the whole history when kk >= m)
+    if (kk < 0) {
+      for (int j = tid; j < n; j += NT) emit(j, j);
+    } else {
+      const int hk = kk >= m ? m : 0;
+      for (int j = tid; j < hk; j += NT) emit(j, j);
+      for (int j = tid; j < w; j += NT) emit(hk + j, m + j);
+    }
+  } else {
+    const float* I = imp + tab.score_off[seg];
+    float* P = pooled + tab.score_off[seg];
+    // ---------------- phase A: this block's pooled scores and their first-level histogram
+    {
+      const int radius = RADIUS >= 0 ? RADIUS : pool_kernel / 2;
+      const bool is_max = pool_mode != SLKV_POOL_AVG;
+      const float fill = is_max ? -INFINITY : 0.f;
+      const float inv_p = 1.f / (float)pool_kernel;
+      const int p0 = blk * kSelBlock;
+      const int cnt = min(kSelBlock, m - p0);
+      float* stage = reinterpret_cast<float*>(cand);      // stage[s] = importance at position p0 - radius + s
+      for (int s = tid; s < cnt + 2 * radius; s += NT) {
+        const int j = p0 - radius + s;
+        stage[s] = (j >= 0 && j < m) ? I[j] : fill;
+      }
+      for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < kSelBlock / NT; ++e) {
+        const int s = e * NT + tid;
+        if (s < cnt) {
+          float a = stage[s];
+          if (RADIUS >= 0) {
+#pragma unroll
+            for (int t = 1; t <= 2 * (RADIUS >= 0 ? RADIUS : 0); ++t) a = is_max ? fmaxf(a, stage[s + t]) : a + stage[s + t];
+          } else {
+            for (int t = 1; t <= 2 * radius; ++t) a = is_max ? fmaxf(a, stage[s + t]) : a + stage[s + t];
+          }
+          if (!is_max) a *= inv_p;
+          st_dev(P + p0 + s, a);
+          atomicAdd(&hist[score_key(a) >> kDigitShift], 1u);
+        }
+      }
+      __syncthreads();
+    }
+    SLKV_STAMP(bid, 1);
+    if (nblk > 1) {
+      // publish the block histogram; the block that arrives last at the ticket adds them up
+      uint32_t* bh = blockhist + (size_t)(tab.hblk[seg] + blk) * kHistBins;
+      for (int i = tid; i < kHistBins; i += NT) st_dev(bh + i, hist[i]);
+      if (!last_arrival(tickets + kTicketSelect + tab.tick[seg], (uint32_t)nblk, &res[0])) return;
+      SLKV_STAMP(bid, 2);
+      const uint32_t* bh0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+      static_assert(kHistBins == 2 * NT, "a thread adds up two bins");
+      uint32_t a0 = 0, a1 = 0;
+      for (int b0 = 0; b0 < nblk; b0 += 8) {              // 16 loads in flight
+        uint32_t v0[8], v1[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int b = min(b0 + u, nblk - 1);
+          v0[u] = ld_dev(bh0 + (size_t)b * kHistBins + tid);
+          v1[u] = ld_dev(bh0 + (size_t)b * kHistBins + NT + tid);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (b0 + u < nblk) {
+            a0 += v0[u];
+            a1 += v1[u];
+          }
+      }
+      hist[tid] = a0;
+      hist[NT + tid] = a1;
+      __syncthreads();
+    } else {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this block's pooled scores are re-read below
+      __syncthreads();
+    }
+
+    SLKV_STAMP(bid, 3);
+    // ---------------- phase B: the k-th largest pooled score of the segment
+    const int rounds = (m + ROUND - 1) / ROUND;
+    const bool multi = rounds > 1;
+    uint32_t key[EPT];
+    auto load_round = [&](int r) __attribute__((always_inline)) {
+      const int base = r * ROUND + wv * (64 * EPT) + lane;
+      float ld[EPT];
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) ld[j] = ld_dev(P + min(base + j * 64, m - 1));
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) key[j] = base + j * 64 < m ? score_key(ld[j]) : kKeyNone;
+    };
+    // f(key) over every score of the segment (rounds beyond the first re-read the pooled array)
+    auto sweep = [&](auto f) __attribute__((always_inline)) {
+      for (int r = 0; r < rounds; ++r) {
+        if (multi) load_round(r);
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) f(key[j]);
+      }
+    };
+    if (!multi) load_round(0);
+    SLKV_STAMP(bid, 4);
+
+    uint32_t k = (uint32_t)kk;
+    select_bin<NT>(hist, k, sh_scan, res);
+    SLKV_STAMP(bid, 5);
+    uint32_t in_range = hist[res[0]];
+    uint32_t lo = res[0] << kDigitShift;
+    uint32_t hi = lo + ((1u << kDigitShift) - 1u);
+    k = res[1];
+    __syncthreads();
+
+    // the scores of the chosen digit, as an unordered list in LDS (if they fit)
+    const bool use_list = in_range <= (uint32_t)kSelCandidates;
+    const uint32_t ncand = in_range;
+    if (use_list) {
+      if (tid == 0) res[2] = 0;
+      __syncthreads();
+      for (int r = 0; r < rounds; ++r) {
+        if (multi) load_round(r);
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) c += (uint32_t)__popcll(__ballot(key[j] >= lo && key[j] <= hi));
+        uint32_t base = 0;
+        if (c) {
+          if (lane == 0) base = atomicAdd(&res[2], c);
+          base = (uint32_t)__shfl((int)base, 0, 64);
+#pragma unroll
+          for (int j = 0; j < EPT; ++j) {
+            const bool in = key[j] >= lo && key[j] <= hi;
+            const unsigned long long mask = __ballot(in);
+            const uint32_t slot = base + lanes_below(mask);
+            if (in && slot < (uint32_t)kSelCandidates) cand[slot] = key[j];
+            base += (uint32_t)__popcll(mask);
+          }
+        }
+      }
+      __syncthreads();
+    }
+    SLKV_STAMP(bid, 6);
+    // narrow [lo, hi] down to one value: 11 bits per level over what is left of the range
+    for (;;) {
+      if (in_range <= (uint32_t)kSelRankMax && (use_list || lo == hi)) {
+        if (lo == hi) break;                              // every score left equals lo
+        // short list: gather the scores still in range, then the k-th largest by counting
+        if (tid == 0) res[3] = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < ncand; i += NT) {
+          const uint32_t kv = cand[i];
+          if (kv >= lo && kv <= hi) {
+            const uint32_t slot = atomicAdd(&res[3], 1u);
+            if (slot < (uint32_t)kSelRankMax) small_list[slot] = kv;
+          }
+        }
+        __syncthreads();
+        const uint32_t ns = min(res[3], (uint32_t)kSelRankMax);
+        if ((uint32_t)tid < ns) {
+          const uint32_t kv = small_list[tid];
+          uint32_t gt = 0, ge = 0;
+          for (uint32_t i = 0; i < ns; ++i) {
+            const uint32_t o = small_list[i];
+            gt += o > kv ? 1u : 0u;
+            ge += o >= kv ? 1u : 0u;
+          }
+          if (gt < k && k <= ge) {   // every thread holding the k-th largest value writes the same pair
+            res[0] = kv;
+            res[1] = k - gt;
+          }
+        }
+        __syncthreads();
+        lo = hi = res[0];
+        k = res[1];
+        __syncthreads();
+        break;
+      }
+      const uint32_t span1 = hi - lo;
+      const int nbits = span1 ? 32 - __clz(span1) : 0;
+      const int shift = nbits > 11 ? nbits - 11 : 0;
+      for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
+      __syncthreads();
+      if (use_list) {
+        for (uint32_t i = tid; i < ncand; i += NT) {
+          const uint32_t kv = cand[i];
+          if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
+        }
+      } else {
+        sweep([&](uint32_t kv) {
+          if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
+        });
+      }
+      __syncthreads();
+      select_bin<NT>(hist, k, sh_scan, res);
+      in_range = hist[res[0]];
+      k = res[1];
+      lo = lo + (res[0] << shift);
+      hi = min(hi, lo + ((1u << shift) - 1u));
+      __syncthreads();
+      if (shift == 0) break;
+    }
+    const uint32_t tau = lo, need_eq = k;
+    SLKV_STAMP(bid, 7);
+
+    // ---------------- ordered compaction: slot = (#greater before) + min(#equal before, need_eq)
+    uint32_t carry_g = 0, carry_e = 0;
+    for (int r = 0; r < rounds; ++r) {
+      if (multi) load_round(r);
+      uint32_t wg = 0, we = 0;
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) {
+        wg += (uint32_t)__popcll(__ballot(key[j] > tau && key[j] != kKeyNone));
+        we += (uint32_t)__popcll(__ballot(key[j] == tau));
+      }
+      if (lane == 0) {
+        sh_wg[wv] = wg;
+        sh_we[wv] = we;
+      }
+      __syncthreads();
+      uint32_t g_before = carry_g, e_before = carry_e, tot_g = 0, tot_e = 0;
+#pragma unroll
+      for (int v2 = 0; v2 < NW; ++v2) {
+        const uint32_t a = sh_wg[v2], b = sh_we[v2];
+        if (v2 < wv) {
+          g_before += a;
+          e_before += b;
+        }
+        tot_g += a;
+        tot_e += b;
+      }
+      if (wg + we) {
+        const int base = r * ROUND + wv * (64 * EPT) + lane;
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+          const bool g = key[j] > tau && key[j] != kKeyNone;
+          const bool e = key[j] == tau;
+          const unsigned long long mg = __ballot(g), me = __ballot(e);
+          if (mg | me) {
+            const uint32_t my_g = g_before + lanes_below(mg);
+            const uint32_t my_e = e_before + lanes_below(me);   // ties are taken in position order
+            if (g) emit((int)(my_g + min(my_e, need_eq)), base + j * 64);
+            else if (e && my_e < need_eq) emit((int)(my_g + my_e), base + j * 64);
+            g_before += (uint32_t)__popcll(mg);
+            e_before += (uint32_t)__popcll(me);
+          }
+        }
+      }
+      carry_g += tot_g;
+      carry_e += tot_e;
+      __syncthreads();
+    }
+    for (int j = tid; j < w; j += NT) emit(kk + j, m + j);
+    SLKV_STAMP(bid, 8);
+  }
+
+  // Small segments copy their K/V rows here (saves the gather launch); larger ones are left
+  // to gather_kernel, which skips the segments handled here.
+  if (kept > 0 && small_seg) {
+    __syncthreads();                                // sh_pos is complete
+    const int64_t tok0 = tab.tok_begin[seg], h = tab.head[seg], row0 = tab.out_off[seg];
+    const int pieces = kept * ga.lanes_per_row;
+    for (int idx = tid; idx < pieces; idx += NT) {
+      const int row = idx / ga.lanes_per_row, c = idx % ga.lanes_per_row;
+      const int64_t tok = tok0 + sh_pos[row];
+      const uint4 kv = *reinterpret_cast<const uint4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + c * 16);
+      const uint4 vv = *reinterpret_cast<const uint4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + c * 16);
+      const int64_t o = ((row0 + row) * ga.lanes_per_row + c) * 16;
+      *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
+      *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
+      if (ga.pos_out && c == 0) ga.pos_out[row0 + row] = ga.pos_in[tok];
+    }
+  }
+  SLKV_STAMP(bid, 9);
+}
+
+// The same selection for launches whose histories all fit one round of kSelRound positions: one
+// workgroup per segment does everything, and the scores never leave its registers between the
+// first load and the last store (no second workgroup to wait for, no re-read).  Thread t owns 32
+// consecutive positions (values reach it through an LDS transposition of coalesced loads), so
+// pooling is a sliding window in registers and the ordered compaction is one block scan of
+// packed (greater, equal) counts plus per-thread bit masks.  The first radix level takes its 11-bit
+// digits relative to the segment's own [min, max] of keys, which spreads the LDS histogram over
+// nearly all bins and leaves few scores in the chosen one.
+constexpr int kResStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * kSelHaloMax) >> 5) + 8;
+constexpr int kResCandidates = 3072;   // scores of one first-level digit that the LDS list can hold
+constexpr size_t kResLdsBytes = (size_t)(kResStageFloats + kResCandidates) * sizeof(float);
 
 __device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
 
 template <int RADIUS, class TAB>   // pooling radius known at compile time (0..3), or -1: any radius, window read from LDS
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
-                                                             int write_pooled, const float* __restrict__ imp,
-                                                             float* __restrict__ pooled, int32_t* __restrict__ kept_idx,
-                                                             int64_t* __restrict__ d_out_offsets, int is_last_group,
-                                                             const GatherArgs ga) {
-  constexpr int NT = kSelThreads, EPT = kSelEPT, ROUND = kSelRound;
+__global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
+                                                                      int write_pooled, const float* __restrict__ imp,
+                                                                      float* __restrict__ pooled, int32_t* __restrict__ kept_idx,
+                                                                      int64_t* __restrict__ d_out_offsets, const GatherArgs ga) {
+  constexpr int NT = kSelThreads, EPT = kSelEPT, ROUND = kSelRound;   // the history is at most ROUND positions
   extern __shared__ float stage[];
   __shared__ uint32_t hist[kHistBins];
+  __shared__ int32_t sh_pos[kInlineGatherRows];
   __shared__ uint32_t sh_scan[NT / 64];
   __shared__ uint32_t res[2];
   __shared__ uint32_t sh_mm[2 * (NT / 64)];
@@ -544,21 +967,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
   const int seg = blockIdx.x;
   const int n = tab.n[seg];
   const int kk = tab.kkeep[seg];
+  const int m = n - w;
+  const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
+  const bool small_seg = kept <= kInlineGatherRows;
   int32_t* out = kept_idx + tab.out_off[seg];
   if (d_out_offsets && tid == 0) {
     d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
-    if (is_last_group && seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
+    if (seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
   }
-  const int m = n - w;
-  bool ranked = false;
-  if (kk < 0) {                                    // whole segment kept
-    for (int j = tid; j < n; j += NT) out[j] = j;
-  } else {
-    for (int j = tid; j < w; j += NT) out[kk + j] = m + j;
-    if (kk >= m) {
-      for (int j = tid; j < m; j += NT) out[j] = j;
-    } else if (kk > 0) {
-      ranked = true;
+  auto emit = [&](int pos, int j) __attribute__((always_inline)) {   // kept position j goes to output slot pos
+    if ((uint32_t)pos < (uint32_t)kept) {
+      out[pos] = j;
+      if (small_seg) sh_pos[pos] = j;
+    }
+  };
+  SLKV_STAMP(128 + seg, 0);
+  if (small_seg)
+    for (int i = tid; i < kInlineGatherRows; i += NT) sh_pos[i] = 0;
+  __syncthreads();
+  const bool ranked = kk > 0 && kk < m;
+  if (!ranked) {
+    if (kk < 0) {
+      for (int j = tid; j < n; j += NT) emit(j, j);
+    } else {
+      for (int j = tid; j < w; j += NT) emit(j, m + j);   // kk == 0: the window alone
     }
   }
   if (ranked) {
@@ -568,14 +1000,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
   const bool is_max = pool_mode != SLKV_POOL_AVG;
   const float fill = is_max ? -INFINITY : 0.f;
   const float inv_p = 1.f / (float)pool_kernel;
-  const int rounds = (m + ROUND - 1) / ROUND;
-  const bool multi = rounds > 1;
 
   float p[EPT];                                    // pooled scores of this thread in the current round
 
-  // pooled scores of round r from the importance array
-  auto pool_round = [&](int r) {
-    const int base = r * ROUND;
+  // pooled scores from the importance array
+  auto pool_all = [&]() {
+    const int base = 0;
     // all loads first (clamped addresses, so none depends on a branch), then the LDS writes
     float ld[EPT + 1];
 #pragma unroll
@@ -631,45 +1061,25 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
     }
     __syncthreads();
   };
-  // pooled scores of round r read back from the pooled array (histories longer than one round)
-  auto reload_round = [&](int r) {
-    const int base = r * ROUND;
-    float ld[EPT];
-#pragma unroll
-    for (int c = 0; c < EPT; ++c) ld[c] = P[min(base + c * NT + tid, m - 1)];
-#pragma unroll
-    for (int c = 0; c < EPT; ++c) stage[pad_idx(c * NT + tid)] = ld[c];
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) p[e] = stage[pad_idx(EPT * tid + e)];
-    __syncthreads();
-  };
-
-  // Keys of the current round: bit patterns of the pooled scores (>= 0, so monotone); positions
-  // past the end of the history get a key above every score.
+  // Keys: bit patterns of the pooled scores (>= 0, so monotone); positions past the end of the
+  // history get a key above every score.
   uint32_t key[EPT];
-  auto make_keys = [&](int r) {
-    const int j0 = r * ROUND + EPT * tid;
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) key[e] = j0 + e < m ? __float_as_uint(p[e]) : 0xffffffffu;
-  };
+  const int j0 = EPT * tid;
 
   // pass 1: pooled scores, their range, and (if asked or needed later) the pooled array
   uint32_t kmin = 0xffffffffu, kmax = 0u;
-  for (int r = 0; r < rounds; ++r) {
-    pool_round(r);
-    make_keys(r);
-    const int j0 = r * ROUND + EPT * tid;
+  pool_all();
+  SLKV_STAMP(128 + seg, 1);
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      kmin = min(kmin, key[e]);
-      if (key[e] != 0xffffffffu) kmax = max(kmax, key[e]);
-    }
-    if (write_pooled || multi) {
+  for (int e = 0; e < EPT; ++e) {
+    key[e] = j0 + e < m ? score_key(p[e]) : kKeyNone;
+    kmin = min(kmin, key[e]);
+    if (key[e] != kKeyNone) kmax = max(kmax, key[e]);
+  }
+  if (write_pooled) {
 #pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (j0 + e < m) P[j0 + e] = p[e];
-    }
+    for (int e = 0; e < EPT; ++e)
+      if (j0 + e < m) P[j0 + e] = p[e];
   }
 #pragma unroll
   for (int dlt = 32; dlt > 0; dlt >>= 1) {
@@ -686,15 +1096,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
     kmin = min(kmin, sh_mm[i]);
     kmax = max(kmax, sh_mm[NT / 64 + i]);
   }
-  if (multi) __threadfence_block();                // the pooled array is re-read by other threads below
   __syncthreads();
 
+  SLKV_STAMP(128 + seg, 2);
   // Radix select on (key - lo) >> shift.  The first level histograms every score; the scores
   // of the chosen digit are then collected in LDS (the staging array) and the remaining
   // levels work on that list.  If the list would not fit, the levels sweep all scores again.
   uint32_t lo = kmin, hi = kmax, k = (uint32_t)kk;
-  uint32_t* cand = reinterpret_cast<uint32_t*>(stage + kSelStageFloats);   // after the staging area
-  constexpr uint32_t kCandCap = kSelCandidates;
+  uint32_t* cand = reinterpret_cast<uint32_t*>(stage + kResStageFloats);   // after the staging area
+  constexpr uint32_t kCandCap = kResCandidates;
   bool use_list = false;
   uint32_t ncand = 0;
   for (int level = 0;; ++level) {
@@ -730,18 +1140,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
         if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
       }
     } else {
-      for (int r = 0; r < rounds; ++r) {
-        if (multi) {
-          reload_round(r);
-          make_keys(r);
-        }
 #pragma unroll
-        for (int e = 0; e < EPT; ++e)
-          if (key[e] >= lo && key[e] <= hi) atomicAdd(&hist[(key[e] - lo) >> shift], 1u);
-      }
+      for (int e = 0; e < EPT; ++e)
+        if (key[e] >= lo && key[e] <= hi) atomicAdd(&hist[(key[e] - lo) >> shift], 1u);
     }
     __syncthreads();
+    if (level == 0) SLKV_STAMP(128 + seg, 3);
     select_bin<NT>(hist, k, sh_scan, res);
+    if (level == 0) SLKV_STAMP(128 + seg, 4);
     const uint32_t bsel = res[0], cnt_sel = hist[bsel];
     k = res[1];
     __syncthreads();
@@ -752,15 +1158,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
       // collect the scores of the chosen digit (their order does not matter for counting)
       if (tid == 0) res[0] = 0;
       __syncthreads();
-      for (int r = 0; r < rounds; ++r) {
-        if (multi) {
-          reload_round(r);
-          make_keys(r);
-        }
 #pragma unroll
-        for (int e = 0; e < EPT; ++e)
-          if (key[e] >= lo && key[e] <= hi) cand[atomicAdd(&res[0], 1u)] = key[e];
-      }
+      for (int e = 0; e < EPT; ++e)
+        if (key[e] >= lo && key[e] <= hi) {
+          const uint32_t slot = atomicAdd(&res[0], 1u);
+          if (slot < kCandCap) cand[slot] = key[e];
+        }
       __syncthreads();
       ncand = res[0];
       use_list = true;
@@ -768,29 +1171,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
     }
   }
   const uint32_t tau = lo, need_eq = k;
+  SLKV_STAMP(128 + seg, 5);
 
-  // ordered compaction: position = (#greater before) + min(#equal before, need_eq)
-  uint32_t carry_g = 0, carry_e = 0;
-  for (int r = 0; r < rounds; ++r) {
-    if (multi) {
-      reload_round(r);
-      make_keys(r);
-    }
-    const int j0 = r * ROUND + EPT * tid;
+  // ordered compaction: slot = (#greater before) + min(#equal before, need_eq)
+  {
     uint32_t gmask = 0, emask = 0;                 // bit e: element e is above / equal to the threshold
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      gmask |= (key[e] > tau && key[e] != 0xffffffffu) ? (1u << e) : 0u;
+      gmask |= (key[e] > tau && key[e] != kKeyNone) ? (1u << e) : 0u;
       emask |= key[e] == tau ? (1u << e) : 0u;
     }
     const uint32_t cg = __popc(gmask), ce = __popc(emask);
-    const uint32_t packed = (ce << 16) | cg;       // a round holds at most 32768 of either
+    const uint32_t packed = (ce << 16) | cg;       // the round holds at most 32768 of either
     const uint32_t incl = block_incl_scan<NT, uint32_t>(packed, sh_scan);
-    if (tid == NT - 1) res[0] = incl;
-    __syncthreads();
-    const uint32_t tot = res[0];
     const uint32_t excl = incl - packed;
-    const uint32_t g_before = carry_g + (excl & 0xffffu), e_before = carry_e + (excl >> 16);
+    const uint32_t g_before = excl & 0xffffu, e_before = excl >> 16;
     // ties are taken in position order: this thread keeps its first `take` equal elements
     uint32_t take = 0;
     if (e_before < need_eq) take = (need_eq - e_before) < ce ? (need_eq - e_before) : ce;
@@ -802,26 +1197,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
     uint32_t pos = g_before + (e_before < need_eq ? e_before : need_eq);
     while (sel) {
       const int e = __ffs(sel) - 1;
-      out[pos++] = j0 + e;
+      emit((int)pos++, j0 + e);
       sel &= sel - 1u;
     }
-    carry_g += tot & 0xffffu;
-    carry_e += tot >> 16;
-    __syncthreads();
   }
+  for (int j = tid; j < w; j += NT) emit(kk + j, m + j);
+  SLKV_STAMP(128 + seg, 6);
   }  // ranked
 
   // Small segments copy their K/V rows here (saves the gather launch); larger ones are left
   // to gather_kernel, which skips the segments handled here.
-  const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
-  if (kept > 0 && kept <= kInlineGatherRows) {
-    __threadfence_block();
-    __syncthreads();                                // the positions written above are visible to the block
+  if (kept > 0 && small_seg) {
+    __syncthreads();                                // sh_pos is complete
     const int64_t tok0 = tab.tok_begin[seg], h = tab.head[seg], row0 = tab.out_off[seg];
     const int pieces = kept * ga.lanes_per_row;
     for (int idx = tid; idx < pieces; idx += NT) {
       const int row = idx / ga.lanes_per_row, c = idx % ga.lanes_per_row;
-      const int64_t tok = tok0 + out[row];
+      const int64_t tok = tok0 + sh_pos[row];
       const uint4 kv = *reinterpret_cast<const uint4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + c * 16);
       const uint4 vv = *reinterpret_cast<const uint4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + c * 16);
       const int64_t o = ((row0 + row) * ga.lanes_per_row + c) * 16;
@@ -830,6 +1222,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
       if (ga.pos_out && c == 0) ga.pos_out[row0 + row] = ga.pos_in[tok];
     }
   }
+  SLKV_STAMP(128 + seg, 7);
 }
 
 // Copies kept rows of K and V (bit copies) into the packed output; one 16-byte lane per piece.
@@ -844,7 +1237,9 @@ __global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const Gather
   if (row >= row1) return;
   const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
   if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by select_kernel
-  const int64_t tok = (int64_t)tab.tok_begin[seg] + kept_idx[row];
+  // (a position outside the segment cannot come out of the selection; clamped all the same, so
+  // that no input can turn into an out-of-bounds read here)
+  const int64_t tok = (int64_t)tab.tok_begin[seg] + min(max(kept_idx[row], 0), max(tab.n[seg] - 1, 0));
   const int64_t h = tab.head[seg];
   const uint4 kv = *reinterpret_cast<const uint4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + c * 16);
   const uint4 vv = *reinterpret_cast<const uint4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + c * 16);
@@ -866,10 +1261,13 @@ __global__ void table_write_kernel(const SegTable part, int s0, const SegTableDe
     dst.qrow_off[s0 + i] = part.qrow_off[i];
     dst.score_off[s0 + i] = part.score_off[i];
     dst.seg_global[s0 + i] = part.seg_global[i];
+    dst.hblk[s0 + i] = part.hblk[i];
+    dst.tick[s0 + i] = part.tick[i];
   }
   if (i <= part.nseg) {
     dst.out_off[s0 + i] = part.out_off[i];
     dst.chunk_begin[s0 + i] = part.chunk_begin[i];
+    dst.blk_begin[s0 + i] = part.blk_begin[i];
   }
 }
 
@@ -896,11 +1294,16 @@ struct Geometry {
 
 struct Plan {
   int R, Rpad, CH;
-  size_t part_bytes, lse_bytes, score_bytes, table_bytes;
-  size_t off_part, off_lse, off_imp, off_pooled, off_table, total_bytes;
+  int64_t hist_blocks;   // block histograms (segments of several selection blocks)
+  int64_t ticketed;      // segments that need a ticket slot
+  size_t part_bytes, lse_bytes, score_bytes, hist_bytes, table_bytes;
+  size_t off_part, off_lse, off_imp, off_pooled, off_hist, off_table, total_bytes;
 };
 
 static bool seg_ranked(int64_t n, int64_t w, int64_t cap) { return n > w && n > cap && cap > w; }
+// key chunks of the scoring passes and blocks of the selection for one segment
+static int64_t seg_chunks(const Seg& s, int w, int64_t ch) { return seg_ranked(s.n, w, s.cap) ? (s.n - w + ch - 1) / ch : 0; }
+static int64_t seg_blocks(const Seg& s, int w) { return seg_ranked(s.n, w, s.cap) ? (s.n - w + kSelBlock - 1) / kSelBlock : 1; }
 
 static void make_plan(const Geometry& g, Plan& p) {
   p.R = (g.Hq / g.Hkv) * g.w;
@@ -919,20 +1322,28 @@ static void make_plan(const Geometry& g, Plan& p) {
   }
   p.CH = (int)ch;
   int64_t chunks = 0;
-  for (const Seg& s : g.segs)
-    if (seg_ranked(s.n, g.w, s.cap)) chunks += (s.n - g.w + ch - 1) / ch;
+  p.hist_blocks = 0;
+  p.ticketed = 0;
+  for (const Seg& s : g.segs) {
+    const int64_t nc = seg_chunks(s, g.w, ch), nb = seg_blocks(s, g.w);
+    chunks += nc;
+    if (nb > 1) p.hist_blocks += nb;
+    if (nc > 1 || nb > 1) p.ticketed += 1;
+  }
   auto align = [](size_t x) { return (x + 255) / 256 * 256; };
-  p.part_bytes = align((size_t)std::max<int64_t>(chunks, 1) * p.Rpad * 2 * sizeof(float));
+  p.part_bytes = align((size_t)std::max<int64_t>(chunks, 1) * p.Rpad * sizeof(float));
   p.lse_bytes = align(std::max<size_t>(g.segs.size(), 1) * p.Rpad * sizeof(float));
   p.score_bytes = align((size_t)std::max<int64_t>(1, g.score_elems) * sizeof(float));
-  p.off_part = 0;
+  p.hist_bytes = align((size_t)p.hist_blocks * kHistBins * sizeof(uint32_t));
+  p.off_part = kTicketBytes;                   // the ticket words come first
   p.off_lse = p.off_part + p.part_bytes;
   p.off_imp = p.off_lse + p.lse_bytes;
   p.off_pooled = p.off_imp + p.score_bytes;
-  p.off_table = p.off_pooled + p.score_bytes;
+  p.off_hist = p.off_pooled + p.score_bytes;
+  p.off_table = p.off_hist + p.hist_bytes;
   // device-resident segment table: only for calls with more segments than one kernel argument holds
   const size_t S = g.segs.size();
-  p.table_bytes = S > (size_t)kMaxSegPerLaunch ? align((9 * S + 2) * sizeof(int32_t)) : 0;
+  p.table_bytes = S > (size_t)kMaxSegPerLaunch ? align((12 * S + 3) * sizeof(int32_t)) : 0;
   p.total_bytes = p.off_table + p.table_bytes;
 }
 
@@ -981,74 +1392,114 @@ static void ragged_geometry(const slkv_ragged_desc* d, Geometry& g) {
 
 template <int DK, int MT, int RB, class TAB>
 static void launch_bf16(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
-                        const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+                        const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
+                        uint32_t* tickets) {
   if (pass == 1)
     hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 1, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
-                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp);
+                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
+                       lse, tickets);
   else
     hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 2, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
-                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp);
+                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
+                       lse, tickets);
 }
 
 template <int DK, class TAB>
 static void launch_bf16_rows(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
-                             const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
-  if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
-  else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
-  else if (p.R <= 256) launch_bf16<DK, 2, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
-  else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
+                             const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
+                             uint32_t* tickets) {
+  if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else if (p.R <= 256) launch_bf16<DK, 2, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
 }
 
 template <class TAB>
 static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
-                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp) {
+                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
+                         uint32_t* tickets) {
   if (g.dtype == SLKV_BF16) {
-    if (g.d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
-    else launch_bf16_rows<64>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp);
+    if (g.d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    else launch_bf16_rows<64>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
   hipLaunchKernelGGL((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
-                     g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp)
+                     g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp, lse, tickets)
     if (g.d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
     else { if (pass == 1) SLKV_F32_LAUNCH(64, 1); else SLKV_F32_LAUNCH(64, 2); }
 #undef SLKV_F32_LAUNCH
   }
 }
 
+template <class TAB>
+static void launch_select(int blocks, hipStream_t st, const TAB& tab, const Geometry& g, const float* imp, float* pooled,
+                          uint32_t* blockhist, uint32_t* tickets, int32_t* kept_idx, int64_t* d_out_offsets,
+                          const GatherArgs& ga) {
+  const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
+  const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
+#define SLKV_SELECT_LAUNCH(RAD)                                                                                        \
+  hipLaunchKernelGGL((select_kernel<RAD, TAB>), dim3(blocks), dim3(kSelThreads), 0, st, tab, g.w, pool_kernel, g.pool, imp, \
+                     pooled, blockhist, tickets, kept_idx, d_out_offsets, ga)
+  switch (radius) {
+    case 0: SLKV_SELECT_LAUNCH(0); break;
+    case 1: SLKV_SELECT_LAUNCH(1); break;
+    case 2: SLKV_SELECT_LAUNCH(2); break;
+    case 3: SLKV_SELECT_LAUNCH(3); break;
+    default: SLKV_SELECT_LAUNCH(-1); break;
+  }
+#undef SLKV_SELECT_LAUNCH
+}
+
+// select_resident_kernel needs more LDS than a kernel gets by default: the limit is raised once per
+// kernel instance and device (not a stream operation; the first call on a device should still
+// not be the one a graph capture records).
 template <int RADIUS, class TAB>
-static hipError_t launch_select_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g,
-                                  bool write_pooled, const float* imp, float* pooled, int32_t* kept_idx,
-                                  int64_t* d_out_offsets, int is_last, const GatherArgs& ga) {
-  // LDS above 64 KB per workgroup has to be requested once per kernel and device
-  static std::atomic<uint64_t> attr_set{0};
-  const size_t lds = (size_t)(kSelStageFloats + kSelCandidates) * sizeof(float);
+static hipError_t launch_select_resident_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
+                                           const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets,
+                                           const GatherArgs& ga) {
+  static std::mutex mu;
+  static uint64_t done = 0;                      // bit per device
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  const uint64_t bit = dev < 64 ? (uint64_t(1) << dev) : 0;
-  if (!(attr_set.load(std::memory_order_relaxed) & bit)) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<RADIUS, TAB>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set.fetch_or(bit, std::memory_order_relaxed);
+  {
+    std::lock_guard<std::mutex> lk(mu);
+    const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t(1) << dev) : 0;
+    if (!(done & bit)) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, TAB>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsBytes);
+      if (e != hipSuccess) return e;
+      done |= bit;
+    }
   }
-  hipLaunchKernelGGL((select_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), lds, st, tab, g.w, g.pool_kernel, g.pool,
-                     (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+  const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
+  hipLaunchKernelGGL((select_resident_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), kResLdsBytes, st, tab, g.w,
+                     pool_kernel, g.pool, (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
   return hipSuccess;
 }
 
 template <class TAB>
-static hipError_t launch_select(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
-                                const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets, int is_last,
-                                const GatherArgs& ga) {
+static hipError_t launch_select_resident(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
+                                         const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets,
+                                         const GatherArgs& ga) {
   const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
   switch (radius) {
-    case 0: return launch_select_r<0>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    case 1: return launch_select_r<1>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    case 2: return launch_select_r<2>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    case 3: return launch_select_r<3>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
-    default: return launch_select_r<-1>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, is_last, ga);
+    case 0: return launch_select_resident_r<0>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
+    case 1: return launch_select_resident_r<1>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
+    case 2: return launch_select_resident_r<2>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
+    case 3: return launch_select_resident_r<3>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
+    default: return launch_select_resident_r<-1>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
   }
+}
+
+// SLKV_SELECT=resident|blocks in the environment forces one selection kernel (tests run both on
+// every shape the resident one covers); default: chosen per call.  0 auto, 1 resident, 2 blocks.
+static int select_mode() {
+  const char* e = std::getenv("SLKV_SELECT");
+  if (!e) return 0;
+  if (!std::strcmp(e, "resident")) return 1;
+  if (!std::strcmp(e, "blocks")) return 2;
+  return 0;
 }
 
 // Checks and launches shared by the two entry points.
@@ -1086,6 +1537,9 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
   if (total_kept >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "kept rows >= 2^31");
   Plan p;
   make_plan(g, p);
+  if (p.ticketed > kTicketSlots)
+    return fail(SLKV_ERR_UNSUPPORTED, "%lld segments span several key chunks or selection blocks (limit %d)",
+                (long long)p.ticketed, kTicketSlots);
   if (workspace_bytes < p.total_bytes)
     return fail(SLKV_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, p.total_bytes);
   if (out_capacity_rows < total_kept)
@@ -1114,27 +1568,36 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
   ga.pos_in = d_pos_in;
   ga.pos_out = d_pos_out;
 
-  // One launch group: the kernels of the pass over the segments one table describes.
-  auto launch_group = [&](const auto& tab, int ns, int chunks, int is_last, bool any_large, int64_t rows) -> slkv_status {
+  uint32_t* tickets = (uint32_t*)ws;
+  uint32_t* blockhist = (uint32_t*)(ws + p.off_hist);
+
+  // The kernels of the pass over the segments one table describes.
+  // Selection kernel: if every history fits one round, the one-workgroup-per-segment kernel;
+  // otherwise the histories are cut into blocks.
+  bool resident_select = select_mode() != 2;
+  for (const Seg& sg : g.segs)
+    if (seg_ranked(sg.n, g.w, sg.cap) && sg.n - g.w > kSelRound) resident_select = false;
+  const int nseg = (int)S;
+  auto launch_group = [&](const auto& tab, int chunks, int blocks, bool any_large, int64_t rows) -> slkv_status {
     using TAB = std::decay_t<decltype(tab)>;
     if (chunks > 0) {
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_STATS, st);
-        launch_score(1, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp);
-      }
-      {
-        ScopedKernelTimer tm(SLKV_K_COMBINE, st);
-        hipLaunchKernelGGL(combine_kernel<TAB>, dim3(ns, (p.Rpad + 15) / 16), dim3(256), 0, st, tab, p.Rpad, part, lse);
+        launch_score(1, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp, tickets);
       }
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_ACCUM, st);
-        launch_score(2, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp);
+        launch_score(2, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp, tickets);
       }
     }
     {
       ScopedKernelTimer tm(SLKV_K_SELECT, st);
-      hipError_t se = launch_select(ns, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets, is_last, ga);
-      if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
+      if (resident_select) {
+        hipError_t se = launch_select_resident(nseg, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets, ga);
+        if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
+      } else {
+        launch_select(blocks, st, tab, g, imp, pooled, blockhist, tickets, d_kept_idx, d_out_offsets, ga);
+      }
     }
     if (any_large) {
       ScopedKernelTimer tm(SLKV_K_GATHER, st);
@@ -1147,7 +1610,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
   };
 
   // Few segments: the table travels as a kernel argument.  More: the per-64 tables are written
-  // to a device-resident table by a small kernel each, and one launch group covers all segments.
+  // to a device-resident table by a small kernel each, and one group of launches covers all segments.
   const bool dev_table = S > kMaxSegPerLaunch;
   SegTableDev dev;
   std::memset(&dev, 0, sizeof(dev));
@@ -1160,20 +1623,21 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
     dev.qrow_off = t; t += S;
     dev.score_off = t; t += S;
     dev.seg_global = t; t += S;
+    dev.hblk = t; t += S;
+    dev.tick = t; t += S;
     dev.out_off = t; t += S + 1;
-    dev.chunk_begin = t;
+    dev.chunk_begin = t; t += S + 1;
+    dev.blk_begin = t;
     dev.nseg = (int32_t)S;
   }
-  int64_t out_run = 0, chunks_run = 0;
-  bool any_large_all = false;
+  // running totals over the call: output rows, key chunks, selection blocks, block histograms, tickets
+  int64_t out_run = 0, chunks = 0, blocks = 0, hist_run = 0, tick_run = 0;
+  bool any_large = false;
   for (int64_t s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
     SegTable tab;
     std::memset(&tab, 0, sizeof(tab));
     const int ns = (int)std::min<int64_t>(kMaxSegPerLaunch, S - s0);
     tab.nseg = ns;
-    int64_t chunks = dev_table ? chunks_run : 0;   // the device table holds prefixes over the whole call
-    const int64_t rows_begin = out_run;
-    bool any_large = false;
     for (int i = 0; i < ns; ++i) {
       const Seg& sg = g.segs[(size_t)(s0 + i)];
       tab.tok_begin[i] = (int32_t)sg.row_begin;
@@ -1187,31 +1651,31 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
       tab.head[i] = sg.head;
       tab.qrow_off[i] = (int32_t)sg.qrow_off;
       tab.score_off[i] = (int32_t)sg.score_off;
-      tab.chunk_begin[i] = (int32_t)chunks;
       tab.seg_global[i] = (int32_t)(s0 + i);
-      if (seg_ranked(sg.n, g.w, sg.cap)) chunks += (sg.n - g.w + p.CH - 1) / p.CH;
-    }
-    if (chunks >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "too many key chunks");
-    tab.out_off[ns] = (int32_t)out_run;
-    tab.chunk_begin[ns] = (int32_t)chunks;
-    tab.total_chunks = (int32_t)chunks;
-    // the remaining entries repeat the end values so that searches stay inside the table
-    for (int i = ns + 1; i <= kMaxSegPerLaunch; ++i) {
-      tab.out_off[i] = tab.out_off[ns];
+      const int64_t nc = seg_chunks(sg, g.w, p.CH), nb = seg_blocks(sg, g.w);
       tab.chunk_begin[i] = (int32_t)chunks;
+      tab.blk_begin[i] = (int32_t)blocks;
+      tab.hblk[i] = (int32_t)hist_run;
+      tab.tick[i] = (int32_t)tick_run;
+      chunks += nc;
+      blocks += nb;
+      if (nb > 1) hist_run += nb;
+      if (nc > 1 || nb > 1) tick_run += 1;
     }
-    if (dev_table) {
-      hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kMaxSegPerLaunch + 64), 0, st, tab, (int)s0, dev);
-      chunks_run = chunks;
-      any_large_all |= any_large;
-    } else {
-      slkv_status gs = launch_group(tab, ns, (int)chunks, 1, any_large, out_run - rows_begin);
-      if (gs != SLKV_OK) return gs;
+    if (chunks >= (int64_t(1) << 31) || blocks >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "too many key chunks");
+    // the remaining entries repeat the end values so that searches stay inside the table
+    for (int i = ns; i <= kMaxSegPerLaunch; ++i) {
+      tab.out_off[i] = (int32_t)out_run;
+      tab.chunk_begin[i] = (int32_t)chunks;
+      tab.blk_begin[i] = (int32_t)blocks;
     }
+    tab.total_chunks = (int32_t)chunks;
+    if (dev_table) hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kMaxSegPerLaunch + 64), 0, st, tab, (int)s0, dev);
+    else return launch_group(tab, (int)chunks, (int)blocks, any_large, out_run);
   }
   if (dev_table) {
-    dev.total_chunks = (int32_t)chunks_run;
-    return launch_group(dev, (int)S, (int)chunks_run, 1, any_large_all, out_run);
+    dev.total_chunks = (int32_t)chunks;
+    return launch_group(dev, (int)chunks, (int)blocks, any_large, out_run);
   }
   return SLKV_OK;
 }
@@ -1237,6 +1701,8 @@ static slkv_status static_scratch(void** out) {
     void* ptr = nullptr;
     e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
     if (e != hipSuccess || !ptr) return fail(SLKV_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    e = hipMemset(ptr, 0, kTicketBytes);      // the counters at its start begin at zero (once; not under capture)
+    if (e != hipSuccess) return fail(SLKV_ERR_HIP, "clearing the static scratch failed: %s", hipGetErrorString(e));
     ptrs[dev] = ptr;
   }
   *out = ptrs[dev];
