@@ -30,5 +30,5 @@ from .compress import (  # noqa: F401
     recompress_layer,
     kept_count,
 )
-from .budgets import allocate_budgets, allocate_budgets_literal, fixed_from_beta  # noqa: F401
-from .behavior import row_weights, finalize_scores, score_heads  # noqa: F401
+from .budgets import allocate_budgets, allocate_budgets_literal, allocate_budgets_per_query_head, fixed_from_beta  # noqa: F401
+from .behavior import row_weights, finalize_scores, harmonic, score_heads, score_heads_modes  # noqa: F401

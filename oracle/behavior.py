@@ -15,6 +15,13 @@ Readings where the paper is silent: K is a parameter (the needle length by
 default); equal weights rank by lower position; a head's scores come from the
 four cells summed over all of its rows (micro average), then divided once;
 0/0 is 0.  Rows are fp32 and are widened to float64 before any sum.
+
+Variants (score_heads_modes): the ablation of Section 4.2 / Table 4 keeps or
+removes each of WO, WD, WS; the paper prints no formula for the ablated score,
+so a removed component is read as the value 0 in steps 5-6.  A "macro"
+aggregation takes SF and LG of every row first, averages them over the head's
+rows and applies step 7 to the two means (the default "micro" aggregation sums
+the cells first).
 """
 
 import numpy as np
@@ -40,12 +47,22 @@ def row_weights(row, needle_start, needle_len, topk):
     return WO, WD, WS, wide
 
 
-def finalize_scores(WO, WD, WS):
-    """Steps 5-7 of Algorithm 1 with 0/0 = 0.  Returns (SF, LG, INF)."""
+def finalize_scores(WO, WD, WS, components=(True, True, True)):
+    """Steps 5-7 of Algorithm 1 with 0/0 = 0.  Returns (SF, LG, INF).
+    components = (use WO, use WD, use WS): a component that is switched off (the
+    "-" entries of Table 4) enters steps 5-6 as 0."""
+    WO = WO if components[0] else 0.0
+    WD = WD if components[1] else 0.0
+    WS = WS if components[2] else 0.0
     SF = WO / (WO + WD) if (WO + WD) > 0.0 else 0.0
     LG = WO / (WO + WS) if (WO + WS) > 0.0 else 0.0
-    INF = 2.0 * SF * LG / (SF + LG) if (SF + LG) > 0.0 else 0.0
+    INF = harmonic(SF, LG)
     return SF, LG, INF
+
+
+def harmonic(SF, LG):
+    """Step 7 of Algorithm 1 (0/0 = 0)."""
+    return 2.0 * SF * LG / (SF + LG) if (SF + LG) > 0.0 else 0.0
 
 
 def score_heads(rows, needle_start, needle_len, topk, acc=None):
@@ -69,4 +86,41 @@ def score_heads(rows, needle_start, needle_len, topk, acc=None):
     for l in range(L):
         for h in range(H):
             scores[l, h] = finalize_scores(acc[l, h, 0], acc[l, h, 1], acc[l, h, 2])
+    return acc, scores
+
+
+def score_heads_modes(rows, needle_start, needle_len, topk, aggregation="micro", components=(True, True, True), acc=None):
+    """As score_heads, with the aggregation over a head's rows and the ablation of Table 4 as
+    parameters.  acc[L, H, 8] = (sum WO, sum WD, sum WS, sum Wide, row count, sum of per-row SF,
+    sum of per-row LG, 0); the per-row SF / LG use the same `components`.
+    aggregation "micro": scores from the summed cells; "macro": SF, LG = means of the per-row
+    values, INF = step 7 on the two means."""
+    if aggregation not in ("micro", "macro"):
+        raise ValueError("aggregation must be 'micro' or 'macro'")
+    rows = np.asarray(rows)
+    L, H, T, _ = rows.shape
+    if acc is None:
+        acc = np.zeros((L, H, 8), dtype=np.float64)
+    for l in range(L):
+        for h in range(H):
+            for t in range(T):
+                WO, WD, WS, wide = row_weights(rows[l, h, t], needle_start, needle_len, topk)
+                sf, lg, _ = finalize_scores(WO, WD, WS, components)
+                acc[l, h, 0] += WO
+                acc[l, h, 1] += WD
+                acc[l, h, 2] += WS
+                acc[l, h, 3] += wide
+                acc[l, h, 4] += 1.0
+                acc[l, h, 5] += sf
+                acc[l, h, 6] += lg
+    scores = np.zeros((L, H, 3), dtype=np.float64)
+    for l in range(L):
+        for h in range(H):
+            if aggregation == "micro":
+                scores[l, h] = finalize_scores(acc[l, h, 0], acc[l, h, 1], acc[l, h, 2], components)
+            else:
+                cnt = acc[l, h, 4]
+                sf = acc[l, h, 5] / cnt if cnt > 0 else 0.0
+                lg = acc[l, h, 6] / cnt if cnt > 0 else 0.0
+                scores[l, h] = (sf, lg, harmonic(sf, lg))
     return acc, scores

@@ -124,3 +124,14 @@ def allocate_budgets_literal(inf_map, Hq, Hkv, avg_budget, fixed_budget):
             row.append(int(math.floor(max(0.0, b) + 0.5)))
         out.append(row)
     return out
+
+
+def allocate_budgets_per_query_head(inf_map, Hq, Hkv, avg_budget, fixed_budget):
+    """Algorithm 2 speaks of the heads of a layer without grouped-query attention in mind; read
+    with its heads = the Hq QUERY heads, every query head gets a capacity (average avg_budget,
+    fixed part fixed_budget, EXACT rule over the L x Hq map), and a KV head, whose cache serves
+    its G query heads, keeps the sum of their capacities.  Returns L rows of Hkv capacities that
+    sum to avg * L * Hq."""
+    per_q = allocate_budgets(inf_map, Hq, Hq, avg_budget, fixed_budget)
+    G = Hq // Hkv
+    return [[sum(row[g * G:(g + 1) * G]) for g in range(Hkv)] for row in per_q]
