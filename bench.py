@@ -22,9 +22,10 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/compress_layer_c3_avg256_rocprofv3.md): either scoring pass, 67600 KiB read + 1000 KiB written.
-MEASURED_TRAFFIC_BYTES = 70.2e6
+# HBM bytes per launch of the dominant kernel (the statistics pass) from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this same command (profiles/compress_layer_c3_avg256_rocprofv3.md, section 2):
+# 67600 KiB read + 130 KiB written.  A counter reading, not something this script can measure.
+MEASURED_TRAFFIC_BYTES = 69.4e6
 
 
 def parse():
@@ -38,8 +39,10 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-recompress", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other budgets of the sweep")
-    ap.add_argument("--other-configs", action="store_true",
-                    help="also time the parity configurations c1, c2 (32 rotating input copies) and c5 (one 1.2 GiB call)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the timing of the parity configurations c1, c2 (32 rotating input copies) and c5 (one 1.2 GiB call)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the on-box copy / GEMM rates printed beside the datasheet peaks")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -127,20 +130,14 @@ def main():
     flops_step = float(np.mean([x[0] for x in work]))
     bytes_step = float(np.mean([x[1] for x in work]))
 
-    # same loop again with an event pair around every kernel launch
+    # same loop again; every kernel launch carries its own start / stop events (the kernel's
+    # execution time, what a rocprofv3 kernel trace reports as its duration)
     nrec = args.steps * 8
     B.slkv_profile_begin(nrec)
     for i in range(args.steps):
         step(args.warmup + i)
     torch.cuda.synchronize()
     recs = B.slkv_profile_end(nrec)
-    # what an event pair reads with nothing between its two records (subtracted below)
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
-    for a_, b_ in pairs:
-        a_.record()
-        b_.record()
-    torch.cuda.synchronize()
-    pair_ms = float(np.median([a_.elapsed_time(b_) for a_, b_ in pairs]))
     per_kernel = {}
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
@@ -150,12 +147,13 @@ def main():
     # launches of the scoring kernels only happen on layers with ranked heads
     ranked_flops = [x[0] for x in work if x[3] > 0]
     flops_launch = float(np.mean(ranked_flops)) if ranked_flops else 0.0
-    dom_ms = kernel_ms.get(dom, float("nan")) - pair_ms
+    dom_ms = kernel_ms.get(dom, float("nan"))
     achieved_tflops = flops_launch / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved_tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5), "empty_event_pair_ms": round(pair_ms, 5),
+                "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5),
+                "timing": "start/stop events carried by each launch of the kernel (hipExtLaunchKernelGGL), mean over the timed steps",
                 "flops_per_launch": flops_launch,
                 # the same launch against the HBM roof (K of the ranked heads read once per pass)
                 "hbm_GBs": round(MEASURED_TRAFFIC_BYTES / (dom_ms * 1e-3) / 1e9, 1) if dom_ms > 0 else 0.0,
@@ -190,8 +188,67 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # The same steps replayed from one HIP graph (every layer's call captured once, in order): what a
+    # serving loop that cannot afford the host-side launch path would run.
+    if not args.no_graph:
+        gs = torch.cuda.Stream()
+        gs.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(gs):
+            for l in range(NL):
+                calls[l].run(dq[l], dk[l], dv[l])
+        torch.cuda.current_stream().wait_stream(gs)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=gs):
+            for l in range(NL):
+                calls[l].run(dq[l], dk[l], dv[l])
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // NL)
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(reps):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        gms = g0.elapsed_time(g1) / (reps * NL)
+        out["graph_replay"] = {"ms_per_step": round(gms, 5), "tokens_per_s": round(n / (gms * 1e-3), 1),
+                               "steps": reps * NL, "graph": "%d layer calls captured into one HIP graph" % NL}
+        del graph
+
+    # What this machine sustains, printed beside the datasheet peaks the fractions are taken against
+    if not args.no_peaks:
+        src = torch.empty(128 << 20, dtype=torch.float32, device=dev).normal_()      # 512 MiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        p1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2 * src.numel() * 4 / (p0.elapsed_time(p1) * 1e-3) / 1e9
+        del src, dst
+        a_ = torch.randn(8192, 8192, dtype=torch.bfloat16, device=dev)
+        b_ = torch.randn(8192, 8192, dtype=torch.bfloat16, device=dev)
+        torch.mm(a_, b_)
+        torch.cuda.synchronize()
+        p0.record()
+        for _ in range(5):
+            torch.mm(a_, b_)
+        p1.record()
+        torch.cuda.synchronize()
+        gemm_tflops = 5 * 2 * 8192.0 ** 3 / (p0.elapsed_time(p1) * 1e-3) / 1e12
+        del a_, b_
+        out["peaks"] = {"hbm_datasheet_GBs": HBM_PEAK_GBS, "mfma_bf16_datasheet_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                        "measured_copy_GBs": round(copy_gbs, 1),
+                        "measured_bf16_gemm_TFLOPs": round(gemm_tflops, 1),
+                        "note": "measured: 512 MiB device copy (read + write bytes) and an 8192^3 bf16 torch.mm on this box"}
+
     # other budgets of the sweep (same inputs, shorter loops)
     sweep = {}
+    sweep_calls = {}
     for avg in wl.C3_BUDGETS:
         if avg == args.avg or args.no_sweep:
             continue
@@ -209,10 +266,10 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
         sweep["avg%d" % avg] = {"ms_per_step": round(ms, 5), "tokens_per_s": round(n / (ms * 1e-3), 1)}
-        del cs
+        sweep_calls[avg] = (bud, cs)
     out["budget_sweep"] = sweep
 
-    if args.other_configs:
+    if not args.no_other_configs:
         def time_config(lay, bud, copies, reps):
             cs = [api.LayerCall(lay.dtype, lay.B, lay.Hq, lay.Hkv, lay.d, lay.w, lay.cu_seqlens, bud) for _ in range(copies)]
             qs = [api.to_device(lay.qwin, lay.dtype) for _ in range(copies)]
@@ -288,7 +345,7 @@ def main():
             api.score_heads(rows, nr.needle_start, nr.needle_len, nr.topk, acc)
         torch.cuda.synchronize()
         recs1 = B.slkv_profile_end(reps * 2)
-        rc_ms = float(np.mean([m_ for k_, m_ in recs1 if k_ == "row_cells"])) - pair_ms
+        rc_ms = float(np.mean([m_ for k_, m_ in recs1 if k_ == "row_cells"]))
         nbytes = rows.numel() * 4
         # bandwidth over the whole call (row kernel + per-head reduction + launch gaps): the conservative figure
         out["stage1"] = {"workload": "c4: 32x32 heads x 16 decode rows x 16384 weights fp32",
@@ -308,24 +365,46 @@ def main():
             cores = len(os.sched_getaffinity(0))
         ncpu = min(args.cpu_layers, NL)
         t0 = time.time()
-        refs = []
+        refs, caches = [], []
         for l in range(ncpu):
             lay = layers[l]
-            refs.append(oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, budgets[l], w, 7))
+            caches.append({})
+            refs.append(oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, budgets[l], w, 7, score_cache=caches[l]))
         cpu_s = time.time() - t0
+        cpu_model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                for line in f:
+                    if line.startswith("model name"):
+                        cpu_model = line.split(":", 1)[1].strip()
+                        break
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": round(ncpu * n / cpu_s, 1), "unit": "tokens/s", "cores": int(cores),
-                               "kind": "oracle", "sample": "%d of the %d layers of the same workload, float64 numpy" % (ncpu, NL)}
-        exact = 0
-        total = 0
-        for l in range(ncpu):
-            calls[l].run(dq[l], dk[l], dv[l])
-            torch.cuda.synchronize()
-            kept = calls[l].kept_idx.cpu().numpy()
-            offs = refs[l]["out_offsets"]
-            for s in range(Hkv):
-                total += 1
-                exact += int(np.array_equal(kept[offs[s]:offs[s + 1]], refs[l]["segments"][s]["kept_idx"]))
-        out["parity"] = {"segments_checked": total, "kept_sets_identical": exact}
+                               "kind": "oracle", "cpu": cpu_model,
+                               "sample": "%d of the %d layers of the same workload, float64 numpy" % (ncpu, NL)}
+
+        # every timed output against the oracle: the main budget and the budgets of the sweep
+        def check(avg, bud_map, call_list, ref_list):
+            exact = total = ranked = 0
+            for l in range(ncpu):
+                call_list[l].run(dq[l], dk[l], dv[l])
+                torch.cuda.synchronize()
+                kept = call_list[l].kept_idx.cpu().numpy()
+                offs = ref_list[l]["out_offsets"]
+                same_rows = (np.array_equal(api.to_host(call_list[l].k_out)[:offs[-1]], ref_list[l]["k_out"])
+                             and np.array_equal(api.to_host(call_list[l].v_out)[:offs[-1]], ref_list[l]["v_out"]))
+                for s_ in range(Hkv):
+                    total += 1
+                    ranked += int(ref_list[l]["segments"][s_]["pooled"] is not None and ref_list[l]["segments"][s_]["k"] > 0)
+                    exact += int(same_rows and np.array_equal(kept[offs[s_]:offs[s_ + 1]], ref_list[l]["segments"][s_]["kept_idx"]))
+            return {"avg_budget": avg, "segments_checked": total, "ranked": ranked, "kept_sets_and_rows_identical": exact}
+        parity = [check(args.avg, budgets, calls, refs)]
+        for avg, (bud, cs) in sorted(sweep_calls.items()):
+            refs2 = [oracle.compress_layer(layers[l].qwin, layers[l].k, layers[l].v, layers[l].cu_seqlens, bud[l], w, 7,
+                                           score_cache=caches[l]) for l in range(ncpu)]
+            parity.append(check(avg, bud, cs, refs2))
+        out["parity"] = parity
     print(json.dumps(out))
 
 

@@ -49,7 +49,7 @@ typedef enum {
 
 typedef enum { SLKV_F32 = 0, SLKV_BF16 = 1 } slkv_dtype;
 typedef enum { SLKV_POOL_NONE = 0, SLKV_POOL_MAX = 1, SLKV_POOL_AVG = 2 } slkv_pool;
-typedef enum { SLKV_BUDGET_EXACT = 0, SLKV_BUDGET_PAPER_LITERAL = 1 } slkv_budget_mode;
+typedef enum { SLKV_BUDGET_EXACT = 0, SLKV_BUDGET_PAPER_LITERAL = 1, SLKV_BUDGET_EXACT_PER_QUERY_HEAD = 2 } slkv_budget_mode;
 
 /* Static description of a status code. */
 const char* slkv_status_str(slkv_status s);
@@ -83,6 +83,31 @@ slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t H, int32_t 
                              void* d_workspace, size_t workspace_bytes, void* hip_stream);
 size_t slkv_score_heads_workspace_bytes(int32_t L, int32_t H, int32_t T, int64_t n);
 
+/* Algorithm 1 with the ablation of Section 4.2 (Table 4) and the aggregation over a head's rows
+ * as parameters.  The paper prints no formula for an ablated score; here a component that is
+ * switched off enters steps 5-6 of Algorithm 1 as 0 (without WS: LG = WO/WO; without WD:
+ * SF = WO/WO; without WO: both 0).
+ *   aggregation SLKV_AGG_MICRO: the head's scores come from its cells summed over all rows
+ *     (what slkv_score_heads does);
+ *   aggregation SLKV_AGG_MACRO: SF and LG are taken per row, averaged over the head's rows
+ *     (every row counts, a row with 0/0 as 0), and step 7 (INF) is applied to the two means.
+ * d_acc [L][H][8] double, in/out, zeroed by the caller before the first call:
+ *   sum WO, sum WD, sum WS, sum Wide, row count, sum of per-row SF, sum of per-row LG, 0
+ *   (the per-row SF / LG use the same components).  Everything else as slkv_score_heads.
+ */
+typedef enum { SLKV_AGG_MICRO = 0, SLKV_AGG_MACRO = 1 } slkv_aggregation;
+typedef struct {
+  uint32_t struct_size;   /* sizeof(slkv_score_params) */
+  int32_t aggregation;    /* slkv_aggregation */
+  int32_t use_wo, use_wd, use_ws;   /* 0 / 1: the "-" / "+" of Table 4 */
+  int32_t reserved;       /* 0 */
+} slkv_score_params;
+slkv_status slkv_score_heads_ex(const slkv_score_params* params, const float* d_rows,
+                                int32_t L, int32_t H, int32_t T, int64_t n,
+                                int64_t needle_start, int32_t needle_len, int32_t topk,
+                                double* d_acc, double* d_scores,
+                                void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------ Stage 2a ----------
  * Eq. (6) / Algorithm 2.  Pure host code, no GPU call.
  *
@@ -99,6 +124,11 @@ size_t slkv_score_heads_workspace_bytes(int32_t L, int32_t H, int32_t T, int64_t
  *            SLKV_BUDGET_PAPER_LITERAL: Algorithm 2 as printed (global normalisation, the 0.01
  *              offset not renormalised, each head rounded half up on its own); does not sum
  *              to the total.
+ *            SLKV_BUDGET_EXACT_PER_QUERY_HEAD: Algorithm 2 read with its heads = the Hq query
+ *              heads (the paper does not mention grouped-query attention): the EXACT rule gives
+ *              every query head a capacity (average avg_budget, fixed part fixed_budget), and
+ *              a KV head, whose cache serves its Hq/Hkv query heads, keeps the sum of theirs;
+ *              the capacities sum to avg*L*Hq.
  * h_budgets  [L][Hkv] out.
  * Errors: NULL, BAD_ARG (sizes, Hq % Hkv, fixed > avg, overflow), BAD_VALUE (INF_sc).
  */

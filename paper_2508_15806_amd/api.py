@@ -88,3 +88,15 @@ def score_heads(rows, needle_start, needle_len, topk, acc=None, stream=None):
     ws = torch.empty((max(B.slkv_score_heads_workspace_bytes(L, H, T, n), 16),), dtype=torch.uint8, device=rows.device)
     B.slkv_score_heads(rows, needle_start, needle_len, topk, acc, scores, ws, stream)
     return acc, scores
+
+
+def score_heads_ex(rows, needle_start, needle_len, topk, aggregation=B.SLKV_AGG_MICRO, components=(True, True, True),
+                   acc=None, stream=None):
+    """As score_heads through slkv_score_heads_ex: acc is [L,H,8]."""
+    L, H, T, n = rows.shape
+    if acc is None:
+        acc = torch.zeros((L, H, 8), dtype=torch.float64, device=rows.device)
+    scores = torch.empty((L, H, 3), dtype=torch.float64, device=rows.device)
+    ws = torch.empty((max(B.slkv_score_heads_workspace_bytes(L, H, T, n), 16),), dtype=torch.uint8, device=rows.device)
+    B.slkv_score_heads_ex(rows, needle_start, needle_len, topk, acc, scores, ws, aggregation, components, stream)
+    return acc, scores

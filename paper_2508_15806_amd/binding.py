@@ -16,12 +16,13 @@ LIB_PATH = os.path.join(_HERE, "libslkv.so")
 
 SLKV_F32, SLKV_BF16 = 0, 1
 SLKV_POOL_NONE, SLKV_POOL_MAX, SLKV_POOL_AVG = 0, 1, 2
-SLKV_BUDGET_EXACT, SLKV_BUDGET_PAPER_LITERAL = 0, 1
+SLKV_BUDGET_EXACT, SLKV_BUDGET_PAPER_LITERAL, SLKV_BUDGET_EXACT_PER_QUERY_HEAD = 0, 1, 2
+SLKV_AGG_MICRO, SLKV_AGG_MACRO = 0, 1
 
 STATUS_NAMES = {0: "SLKV_OK", 1: "SLKV_ERR_NULL", 2: "SLKV_ERR_BAD_ARG", 3: "SLKV_ERR_BAD_VALUE",
                 4: "SLKV_ERR_UNSUPPORTED", 5: "SLKV_ERR_WORKSPACE", 6: "SLKV_ERR_CAPACITY", 7: "SLKV_ERR_HIP"}
 
-EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads",
+EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads", "slkv_score_heads_ex",
            "slkv_score_heads_workspace_bytes", "slkv_allocate_budgets", "slkv_fixed_from_beta",
            "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer", "slkv_compress_layer_static",
            "slkv_recompress_sizes", "slkv_recompress_workspace_bytes", "slkv_recompress_layer",
@@ -38,6 +39,11 @@ class SlkvError(RuntimeError):
 
 class KernelTime(C.Structure):
     _fields_ = [("kernel", C.c_int32), ("ms", C.c_float)]
+
+
+class ScoreParams(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("aggregation", C.c_int32), ("use_wo", C.c_int32), ("use_wd", C.c_int32),
+                ("use_ws", C.c_int32), ("reserved", C.c_int32)]
 
 
 class LayerDesc(C.Structure):
@@ -103,6 +109,8 @@ def lib():
         L.slkv_score_heads.restype = C.c_int
         L.slkv_score_heads.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.slkv_score_heads_ex.restype = C.c_int
+        L.slkv_score_heads_ex.argtypes = [C.POINTER(ScoreParams)] + L.slkv_score_heads.argtypes
         L.slkv_profile_begin.restype = C.c_int
         L.slkv_profile_begin.argtypes = [C.c_int32]
         L.slkv_profile_end.restype = C.c_int
@@ -234,6 +242,17 @@ def slkv_score_heads(rows, needle_start, needle_len, topk, acc, scores, workspac
     _check(lib().slkv_score_heads(_ptr(rows), L, H, T, n, int(needle_start), int(needle_len), int(topk), _ptr(acc),
                                   _ptr(scores), _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                   _stream(stream)))
+
+
+def slkv_score_heads_ex(rows, needle_start, needle_len, topk, acc, scores, workspace, aggregation=SLKV_AGG_MICRO,
+                        components=(True, True, True), stream=None):
+    """As slkv_score_heads with acc [L, H, 8]; aggregation and the (WO, WD, WS) switches of the ablation."""
+    L, H, T, n = rows.shape
+    prm = ScoreParams(C.sizeof(ScoreParams), int(aggregation), int(bool(components[0])), int(bool(components[1])),
+                      int(bool(components[2])), 0)
+    _check(lib().slkv_score_heads_ex(C.byref(prm), _ptr(rows), L, H, T, n, int(needle_start), int(needle_len), int(topk),
+                                     _ptr(acc), _ptr(scores), _ptr(workspace),
+                                     int(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
 def slkv_profile_begin(max_records):

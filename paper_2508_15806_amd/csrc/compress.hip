@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "device_utils.h"
+#include "launch.h"
 #include "slkv_internal.h"
 
 // Development aid, compiled only with -DSLKV_TRACE: clock stamps of chosen workgroups.
@@ -1395,11 +1396,11 @@ static void launch_bf16(int pass, int grid, hipStream_t st, const TAB& tab, cons
                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                         uint32_t* tickets) {
   if (pass == 1)
-    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 1, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
                        (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
                        lse, tickets);
   else
-    hipLaunchKernelGGL((score_bf16_kernel<DK, MT, RB, 2, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
                        (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
                        lse, tickets);
 }
@@ -1423,7 +1424,7 @@ static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, con
     else launch_bf16_rows<64>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
-  hipLaunchKernelGGL((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
+  SLKV_LAUNCH((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
                      g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp, lse, tickets)
     if (g.d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
     else { if (pass == 1) SLKV_F32_LAUNCH(64, 1); else SLKV_F32_LAUNCH(64, 2); }
@@ -1438,7 +1439,7 @@ static void launch_select(int blocks, hipStream_t st, const TAB& tab, const Geom
   const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
   const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
 #define SLKV_SELECT_LAUNCH(RAD)                                                                                        \
-  hipLaunchKernelGGL((select_kernel<RAD, TAB>), dim3(blocks), dim3(kSelThreads), 0, st, tab, g.w, pool_kernel, g.pool, imp, \
+  SLKV_LAUNCH((select_kernel<RAD, TAB>), dim3(blocks), dim3(kSelThreads), 0, st, tab, g.w, pool_kernel, g.pool, imp, \
                      pooled, blockhist, tickets, kept_idx, d_out_offsets, ga)
   switch (radius) {
     case 0: SLKV_SELECT_LAUNCH(0); break;
@@ -1473,7 +1474,7 @@ static hipError_t launch_select_resident_r(int ns, hipStream_t st, const TAB& ta
     }
   }
   const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
-  hipLaunchKernelGGL((select_resident_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), kResLdsBytes, st, tab, g.w,
+  SLKV_LAUNCH((select_resident_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), kResLdsBytes, st, tab, g.w,
                      pool_kernel, g.pool, (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
   return hipSuccess;
 }
@@ -1602,7 +1603,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
     if (any_large) {
       ScopedKernelTimer tm(SLKV_K_GATHER, st);
       const int64_t threads = rows * lanes_per_row;
-      hipLaunchKernelGGL(gather_kernel<TAB>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx);
+      SLKV_LAUNCH(gather_kernel<TAB>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
@@ -1670,7 +1671,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
       tab.blk_begin[i] = (int32_t)blocks;
     }
     tab.total_chunks = (int32_t)chunks;
-    if (dev_table) hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kMaxSegPerLaunch + 64), 0, st, tab, (int)s0, dev);
+    if (dev_table) SLKV_LAUNCH(table_write_kernel, dim3(1), dim3(kMaxSegPerLaunch + 64), 0, st, tab, (int)s0, dev);
     else return launch_group(tab, (int)chunks, (int)blocks, any_large, out_run);
   }
   if (dev_table) {

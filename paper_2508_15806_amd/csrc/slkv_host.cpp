@@ -3,6 +3,7 @@
 #include "slkv_internal.h"
 
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -114,7 +115,7 @@ const char* slkv_status_str(slkv_status s) {
 
 const char* slkv_last_error(void) { return g_err; }
 
-int32_t slkv_version(void) { return 1001; }
+int32_t slkv_version(void) { return 1002; }
 
 int32_t slkv_fixed_from_beta(int32_t avg_budget, double beta) {
   if (avg_budget < 0 || !(beta >= 1.0)) return -1;
@@ -167,10 +168,27 @@ extern "C" slkv_status slkv_allocate_budgets(const double* h_inf, int32_t L, int
   if ((int64_t)L * Hkv > (1 << 20)) return fail(SLKV_ERR_BAD_ARG, "L * Hkv > 2^20");
   if (avg_budget < 0 || avg_budget > (1 << 24)) return fail(SLKV_ERR_BAD_ARG, "avg_budget outside 0..2^24");
   if (fixed_budget < 0 || fixed_budget > avg_budget) return fail(SLKV_ERR_BAD_ARG, "need 0 <= fixed <= avg");
-  if (mode != SLKV_BUDGET_EXACT && mode != SLKV_BUDGET_PAPER_LITERAL) return fail(SLKV_ERR_BAD_ARG, "unknown mode %d", mode);
+  if (mode != SLKV_BUDGET_EXACT && mode != SLKV_BUDGET_PAPER_LITERAL && mode != SLKV_BUDGET_EXACT_PER_QUERY_HEAD)
+    return fail(SLKV_ERR_BAD_ARG, "unknown mode %d", mode);
   for (int64_t i = 0; i < (int64_t)L * Hq; ++i) {
     double v = h_inf[i];
     if (!(v >= 0.0 && v <= 1.0)) return fail(SLKV_ERR_BAD_VALUE, "INF_sc[%lld] = %g outside [0,1]", (long long)i, v);
+  }
+  if (mode == SLKV_BUDGET_EXACT_PER_QUERY_HEAD) {
+    // Algorithm 2 over the query heads (exact rule), then a KV head keeps the sum of its group
+    if ((int64_t)L * Hq > (1 << 20)) return fail(SLKV_ERR_BAD_ARG, "L * Hq > 2^20");
+    std::vector<int32_t> per_q((size_t)L * Hq);
+    slkv_status st = slkv_allocate_budgets(h_inf, L, Hq, Hq, avg_budget, fixed_budget, SLKV_BUDGET_EXACT, per_q.data());
+    if (st != SLKV_OK) return st;
+    const int Gq = Hq / Hkv;
+    for (int l = 0; l < L; ++l)
+      for (int g = 0; g < Hkv; ++g) {
+        int64_t acc = 0;
+        for (int t = 0; t < Gq; ++t) acc += per_q[(size_t)l * Hq + (size_t)g * Gq + t];
+        if (acc > INT32_MAX) return fail(SLKV_ERR_BAD_ARG, "capacity overflow");
+        h_budgets[(size_t)l * Hkv + g] = (int32_t)acc;
+      }
+    return SLKV_OK;
   }
   const int G = Hq / Hkv;
   // group mean: the INF_sc of the G query heads sharing a KV head, summed left to right, / G

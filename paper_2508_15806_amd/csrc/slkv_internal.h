@@ -23,16 +23,19 @@ int64_t kept_rows(int64_t n, int64_t w, int64_t cap);
 slkv_status validate_desc(const slkv_layer_desc* d);
 slkv_status validate_ragged_desc(const slkv_ragged_desc* d);
 
-// Records a HIP event pair around one kernel launch while profiling is on (see
-// slkv_profile_begin); does nothing otherwise.
+// Kernel timing (slkv_profile_begin / _end).  A ScopedKernelTimer names the kernel that the
+// launches inside its scope belong to; while profiling is on, profile_events() hands such a
+// launch a pair of events that the launch itself carries (start and end of the kernel's own
+// execution, without the launch gap an event recorded on the stream would include).
 class ScopedKernelTimer {
  public:
-  ScopedKernelTimer(int kernel_id, void* stream);
+  explicit ScopedKernelTimer(int kernel_id, void* stream = nullptr);
   ~ScopedKernelTimer();
  private:
-  int slot_;
-  void* stream_;
+  int prev_;
 };
+// False when profiling is off, no kernel is named or the record pool is used up.
+bool profile_events(void** start_event, void** stop_event);
 
 }  // namespace slkv
 

@@ -6,6 +6,7 @@
 #include <cmath>
 
 #include "device_utils.h"
+#include "launch.h"
 #include "slkv_internal.h"
 
 namespace slkv {
@@ -310,22 +311,50 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
   }
 }
 
-// One thread per head: adds the head's T rows (in order) into the accumulators and
-// finalises SF, LG, INF (Algorithm 1, steps 5-7; 0/0 = 0).
-__global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t heads, int32_t T,
-                                   double* __restrict__ acc, double* __restrict__ scores) {
+// Steps 5-7 of Algorithm 1 (0/0 = 0); a component that is switched off enters as 0.
+__device__ __forceinline__ void sf_lg(double WO, double WD, double WS, int use_wo, int use_wd, int use_ws, double& SF,
+                                      double& LG) {
+  WO = use_wo ? WO : 0.0;
+  WD = use_wd ? WD : 0.0;
+  WS = use_ws ? WS : 0.0;
+  SF = (WO + WD) > 0.0 ? WO / (WO + WD) : 0.0;
+  LG = (WO + WS) > 0.0 ? WO / (WO + WS) : 0.0;
+}
+
+// One thread per head: adds the head's T rows (in order) into the accumulators and finalises
+// SF, LG, INF (Algorithm 1, steps 5-7).  STRIDE 5: the accumulators of slkv_score_heads;
+// STRIDE 8: those of slkv_score_heads_ex, which also carry the sums of the per-row SF and LG.
+template <int STRIDE>
+__global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t heads, int32_t T, double* __restrict__ acc,
+                                   double* __restrict__ scores, int macro, int use_wo, int use_wd, int use_ws) {
   const int hd = blockIdx.x * blockDim.x + threadIdx.x;
   if (hd >= heads) return;
-  double a[4] = {0.0, 0.0, 0.0, 0.0};
-  for (int t = 0; t < T; ++t)
-    for (int c = 0; c < 4; ++c) a[c] += cells[((int64_t)hd * T + t) * 4 + c];
-  double* A = acc + (int64_t)hd * 5;
-  for (int c = 0; c < 4; ++c) A[c] += a[c];
+  double a[4] = {0.0, 0.0, 0.0, 0.0}, sf_sum = 0.0, lg_sum = 0.0;
+  for (int t = 0; t < T; ++t) {
+    const double* c = cells + ((int64_t)hd * T + t) * 4;
+    for (int i = 0; i < 4; ++i) a[i] += c[i];
+    if (STRIDE == 8) {
+      double sf, lg;
+      sf_lg(c[0], c[1], c[2], use_wo, use_wd, use_ws, sf, lg);
+      sf_sum += sf;
+      lg_sum += lg;
+    }
+  }
+  double* A = acc + (int64_t)hd * STRIDE;
+  for (int i = 0; i < 4; ++i) A[i] += a[i];
   A[4] += (double)T;
+  if (STRIDE == 8) {
+    A[5] += sf_sum;
+    A[6] += lg_sum;
+  }
   if (scores) {
-    const double WO = A[0], WD = A[1], WS = A[2];
-    const double SF = (WO + WD) > 0.0 ? WO / (WO + WD) : 0.0;
-    const double LG = (WO + WS) > 0.0 ? WO / (WO + WS) : 0.0;
+    double SF, LG;
+    if (STRIDE == 8 && macro) {
+      SF = A[4] > 0.0 ? A[5] / A[4] : 0.0;
+      LG = A[4] > 0.0 ? A[6] / A[4] : 0.0;
+    } else {
+      sf_lg(A[0], A[1], A[2], use_wo, use_wd, use_ws, SF, LG);
+    }
     const double INF = (SF + LG) > 0.0 ? 2.0 * SF * LG / (SF + LG) : 0.0;
     scores[(int64_t)hd * 3 + 0] = SF;
     scores[(int64_t)hd * 3 + 1] = LG;
@@ -343,10 +372,11 @@ extern "C" size_t slkv_score_heads_workspace_bytes(int32_t L, int32_t H, int32_t
   return (size_t)L * H * T * 4 * sizeof(double);
 }
 
-extern "C" slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t H, int32_t T, int64_t n,
-                                        int64_t needle_start, int32_t needle_len, int32_t topk, double* d_acc,
-                                        double* d_scores, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  clear_error();
+namespace {
+
+slkv_status run_score_heads(const float* d_rows, int32_t L, int32_t H, int32_t T, int64_t n, int64_t needle_start,
+                            int32_t needle_len, int32_t topk, double* d_acc, double* d_scores, void* d_workspace,
+                            size_t workspace_bytes, void* hip_stream, const slkv_score_params* prm) {
   if (!d_rows || !d_acc || !d_workspace) return fail(SLKV_ERR_NULL, "d_rows, d_acc and d_workspace are required");
   if (L < 1 || H < 1 || T < 1 || n < 1) return fail(SLKV_ERR_BAD_ARG, "L, H, T, n must be >= 1");
   if (n >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "n >= 2^31");
@@ -365,20 +395,53 @@ extern "C" slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t 
   double* cells = (double*)d_workspace;
   const bool resident = (n % 4 == 0) && n >= 4 && n <= (int64_t)kS1Threads * kS1Resident && topk <= kWave;
   {
-  ScopedKernelTimer tm(SLKV_K_ROW_CELLS, st);
-  if (resident)
-    hipLaunchKernelGGL(row_cells_kernel<true>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, (int32_t)n,
-                       (int32_t)needle_start, needle_len, topk, cells);
-  else
-    hipLaunchKernelGGL(row_cells_kernel<false>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, (int32_t)n,
-                       (int32_t)needle_start, needle_len, topk, cells);
+    ScopedKernelTimer tm(SLKV_K_ROW_CELLS, st);
+    if (resident)
+      SLKV_LAUNCH(row_cells_kernel<true>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, (int32_t)n,
+                  (int32_t)needle_start, needle_len, topk, cells);
+    else
+      SLKV_LAUNCH(row_cells_kernel<false>, dim3((unsigned)nrows), dim3(kS1Threads), 0, st, d_rows, (int32_t)n,
+                  (int32_t)needle_start, needle_len, topk, cells);
   }
   const int heads = L * H;
   {
     ScopedKernelTimer tm(SLKV_K_HEAD_REDUCE, st);
-    hipLaunchKernelGGL(head_reduce_kernel, dim3((heads + 127) / 128), dim3(128), 0, st, cells, heads, T, d_acc, d_scores);
+    if (prm)
+      SLKV_LAUNCH(head_reduce_kernel<8>, dim3((heads + 127) / 128), dim3(128), 0, st, (const double*)cells, heads, T, d_acc,
+                  d_scores, (int)(prm->aggregation == SLKV_AGG_MACRO), prm->use_wo, prm->use_wd, prm->use_ws);
+    else
+      SLKV_LAUNCH(head_reduce_kernel<5>, dim3((heads + 127) / 128), dim3(128), 0, st, (const double*)cells, heads, T, d_acc,
+                  d_scores, 0, 1, 1, 1);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
   return SLKV_OK;
+}
+
+}  // namespace
+
+extern "C" slkv_status slkv_score_heads(const float* d_rows, int32_t L, int32_t H, int32_t T, int64_t n,
+                                        int64_t needle_start, int32_t needle_len, int32_t topk, double* d_acc,
+                                        double* d_scores, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  return run_score_heads(d_rows, L, H, T, n, needle_start, needle_len, topk, d_acc, d_scores, d_workspace, workspace_bytes,
+                         hip_stream, nullptr);
+}
+
+extern "C" slkv_status slkv_score_heads_ex(const slkv_score_params* params, const float* d_rows, int32_t L, int32_t H,
+                                           int32_t T, int64_t n, int64_t needle_start, int32_t needle_len, int32_t topk,
+                                           double* d_acc, double* d_scores, void* d_workspace, size_t workspace_bytes,
+                                           void* hip_stream) {
+  clear_error();
+  if (!params) return fail(SLKV_ERR_NULL, "params is NULL");
+  if (params->struct_size != sizeof(slkv_score_params))
+    return fail(SLKV_ERR_BAD_ARG, "params.struct_size %u != %zu", params->struct_size, sizeof(slkv_score_params));
+  if (params->aggregation != SLKV_AGG_MICRO && params->aggregation != SLKV_AGG_MACRO)
+    return fail(SLKV_ERR_BAD_ARG, "unknown aggregation %d", params->aggregation);
+  const int32_t flags[3] = {params->use_wo, params->use_wd, params->use_ws};
+  for (int32_t f : flags)
+    if (f != 0 && f != 1) return fail(SLKV_ERR_BAD_ARG, "use_wo / use_wd / use_ws must be 0 or 1");
+  if (params->reserved != 0) return fail(SLKV_ERR_BAD_ARG, "params.reserved must be 0");
+  return run_score_heads(d_rows, L, H, T, n, needle_start, needle_len, topk, d_acc, d_scores, d_workspace, workspace_bytes,
+                         hip_stream, params);
 }

@@ -1,4 +1,5 @@
-// Optional per-kernel timing with HIP events (slkv_profile_begin / slkv_profile_end).
+// Optional per-kernel timing (slkv_profile_begin / slkv_profile_end): every timed launch carries its
+// own start / stop events (hipExtLaunchKernelGGL), so a record is the kernel's execution time.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -18,21 +19,25 @@ std::vector<Rec> g_pool;   // events created by slkv_profile_begin
 size_t g_used = 0;
 }  // namespace
 
-namespace slkv {
-
-ScopedKernelTimer::ScopedKernelTimer(int id, void* stream) : slot_(-1), stream_(stream) {
-  if (!g_on.load(std::memory_order_relaxed)) return;
-  std::lock_guard<std::mutex> lk(g_mu);
-  if (!g_on.load(std::memory_order_relaxed) || g_used >= g_pool.size()) return;
-  slot_ = (int)g_used++;
-  g_pool[slot_].id = id;
-  (void)hipEventRecord(g_pool[slot_].a, (hipStream_t)stream_);
+namespace {
+thread_local int tl_kernel_id = -1;   // kernel named by the innermost ScopedKernelTimer of this thread
 }
 
-ScopedKernelTimer::~ScopedKernelTimer() {
-  if (slot_ < 0) return;
+namespace slkv {
+
+ScopedKernelTimer::ScopedKernelTimer(int id, void*) : prev_(tl_kernel_id) { tl_kernel_id = id; }
+
+ScopedKernelTimer::~ScopedKernelTimer() { tl_kernel_id = prev_; }
+
+bool profile_events(void** start_event, void** stop_event) {
+  if (tl_kernel_id < 0 || !g_on.load(std::memory_order_relaxed)) return false;
   std::lock_guard<std::mutex> lk(g_mu);
-  (void)hipEventRecord(g_pool[slot_].b, (hipStream_t)stream_);
+  if (!g_on.load(std::memory_order_relaxed) || g_used >= g_pool.size()) return false;
+  Rec& r = g_pool[g_used++];
+  r.id = tl_kernel_id;
+  *start_event = (void*)r.a;
+  *stop_event = (void*)r.b;
+  return true;
 }
 
 }  // namespace slkv

@@ -102,3 +102,22 @@ def test_config4_full_launch_shape_sampled_heads():
         np.testing.assert_allclose(acc[l, h], racc[0, 0], rtol=1e-12, atol=1e-15)
         np.testing.assert_allclose(scores[l, h], rsc[0, 0], rtol=1e-11, atol=1e-15)
     assert (acc[..., 4] == 16).all()
+
+
+@pytest.mark.parametrize("agg,comps", [("micro", (True, True, True)), ("macro", (True, True, True)),
+                                       ("micro", (True, True, False)), ("micro", (True, False, True)),
+                                       ("macro", (True, False, True)), ("micro", (False, True, True)),
+                                       ("macro", (True, False, False))])
+def test_aggregation_and_ablation_modes(agg, comps):
+    import torch
+    from paper_2508_15806_amd import api, binding as B
+    nr = wl.config4(L=2, H=5, T=7, n=4096, seed_extra=11)
+    rows = torch.from_numpy(nr.rows).cuda()
+    mode = B.SLKV_AGG_MACRO if agg == "macro" else B.SLKV_AGG_MICRO
+    acc, sc = api.score_heads_ex(rows, nr.needle_start, nr.needle_len, nr.topk, mode, comps)
+    acc, sc = api.score_heads_ex(rows, nr.needle_start, nr.needle_len, nr.topk, mode, comps, acc=acc)   # accumulates
+    torch.cuda.synchronize()
+    racc, rsc = oracle.score_heads_modes(nr.rows, nr.needle_start, nr.needle_len, nr.topk, agg, comps)
+    racc, rsc = oracle.score_heads_modes(nr.rows, nr.needle_start, nr.needle_len, nr.topk, agg, comps, acc=racc)
+    np.testing.assert_allclose(acc.cpu().numpy(), racc, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(sc.cpu().numpy(), rsc, rtol=1e-11, atol=1e-15)

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert B.slkv_version() == 1001
+    assert B.slkv_version() == 1002
     assert L.slkv_status_str(0) == b"ok"
 
 
@@ -206,3 +206,32 @@ def test_recompress_rejects_before_touching_the_gpu():
     bad = B.RaggedDesc()
     assert L.slkv_recompress_layer(C.byref(bad), fake, fake, fake, null, fake, fake, fake, null, null, null, null,
                                    C.c_int64(1000), fake, big, null) == 2                       # struct_size
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_budgets_per_query_head_match_oracle(seed):
+    rng = np.random.default_rng(100 + seed)
+    L, Hkv, G = int(rng.integers(1, 33)), int(rng.integers(1, 9)), int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * G
+    inf = [rng.random((L, Hq)), wl.inf_spiky((seed, 3), L, Hq), wl.inf_beta((seed, 4), L, Hq)][seed % 3]
+    avg, fixed = int(rng.integers(1, 2000)), 0
+    fixed = int(rng.integers(0, avg + 1))
+    got = B.slkv_allocate_budgets(inf, Hkv, avg, fixed, B.SLKV_BUDGET_EXACT_PER_QUERY_HEAD)
+    assert got.tolist() == oracle.allocate_budgets_per_query_head(np.asarray(inf).tolist(), Hq, Hkv, avg, fixed)
+    assert int(got.sum()) == avg * L * Hq
+
+
+def test_score_heads_ex_rejects_bad_params_before_any_gpu_call():
+    L = B.lib()
+    fake = C.c_void_p(4096)
+    good = B.ScoreParams(C.sizeof(B.ScoreParams), 0, 1, 1, 1, 0)
+    def call(prm, rows=fake, topk=4):
+        return L.slkv_score_heads_ex(C.byref(prm) if prm is not None else None, rows, 1, 1, 1, 64, 0, 4, topk, fake, None,
+                                     fake, 1 << 20, None)
+    assert call(None) == 1                                                        # NULL params
+    assert call(B.ScoreParams(8, 0, 1, 1, 1, 0)) == 2                             # struct_size
+    assert call(B.ScoreParams(C.sizeof(B.ScoreParams), 2, 1, 1, 1, 0)) == 2       # aggregation
+    assert call(B.ScoreParams(C.sizeof(B.ScoreParams), 0, 1, 3, 1, 0)) == 2       # switch not 0/1
+    assert call(B.ScoreParams(C.sizeof(B.ScoreParams), 0, 1, 1, 1, 7)) == 2       # reserved
+    assert call(good, rows=None) == 1                                             # NULL rows
+    assert call(good, topk=0) == 2                                                # topk
