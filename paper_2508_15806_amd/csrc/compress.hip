@@ -46,9 +46,9 @@ struct SegTable {
   int32_t score_off[kMaxSegPerLaunch];   // offset of the segment in the importance / pooled arrays
   int32_t chunk_begin[kMaxSegPerLaunch + 1];  // prefix of key-chunk counts (0 chunks when not ranked)
   int32_t seg_global[kMaxSegPerLaunch];  // index b*Hkv + h
-  int32_t blk_begin[kMaxSegPerLaunch + 1];    // prefix of selection-block counts (one block when not ranked)
-  int32_t hblk[kMaxSegPerLaunch];        // first block histogram of the segment (segments of several blocks)
-  int32_t tick[kMaxSegPerLaunch];        // ticket slot of the segment (segments of several chunks or blocks)
+  int32_t blk_begin[kMaxSegPerLaunch + 1];    // prefix of selection-block counts (no block when not ranked)
+  int32_t hblk[kMaxSegPerLaunch];        // first block histogram of the segment
+  int32_t tick[kMaxSegPerLaunch];        // ticket slot of the segment (segments of several key chunks)
 };
 
 // The same table in device memory, for calls with more segments than fit a kernel argument.
@@ -60,10 +60,9 @@ struct SegTableDev {
 };
 
 // The workspace starts with ticket words (zero between calls): slot t counts the key chunks of a
-// segment that have finished the statistics pass, slot kTicketSelect + t its selection blocks.
-constexpr int kTicketSlots = 8192;
-constexpr int kTicketSelect = kTicketSlots;
-constexpr size_t kTicketBytes = 2 * (size_t)kTicketSlots * sizeof(uint32_t);
+// segment that have finished the statistics pass.
+constexpr int kTicketSlots = 16384;
+constexpr size_t kTicketBytes = (size_t)kTicketSlots * sizeof(uint32_t);
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
@@ -129,7 +128,7 @@ __device__ __forceinline__ bool last_arrival(uint32_t* ticket, uint32_t count, u
 // only the additions run in chunk order, so the result does not depend on timing.
 __device__ __forceinline__ void segment_lse(int c0, int c1, int seg, int Rpad, const float* __restrict__ part,
                                             float* __restrict__ lse) {
-  constexpr int NB = 32;
+  constexpr int NB = 64;   // as many loads as a wave can have in flight
   for (int row = threadIdx.x; row < Rpad; row += blockDim.x) {
     float mm = -INFINITY, ss = 0.f;
     for (int c = c0; c < c1; c += NB) {
@@ -574,19 +573,22 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
 // Pooling + top-k (Algorithm 3, steps 7-8).  Writes the kept positions: history positions
 // ascending, then the window.
 //
-// A segment's history is cut into blocks of kSelBlock positions, one 1024-thread workgroup each.
-//   Phase A (every block): pool the block's importance scores (halo from the neighbours), write
-//     the pooled scores, histogram their leading 11 key bits, publish the histogram.
-//   Phase B (the block of a segment that arrives last at the segment's ticket; a one-block
-//     segment goes straight on): add the block histograms, pick the digit that holds the k-th
-//     largest score, collect that digit's scores in LDS and narrow them down to the exact k-th
-//     largest value tau and the number of scores equal to tau that belong to the top k (ties go
-//     to lower positions); then one ordered compaction of the positions with score > tau, or
-//     == tau among the first `need_eq`.
-// Keys are the bit patterns of the pooled scores (>= 0, so monotone).  In phase B a wave owns 2048
-// consecutive positions of a round of 32768, lane l the positions 64*j + l (j < 32): ballots are in
+// Histories longer than one round of kSelRound positions take two kernels:
+//   select_pool_kernel: the history is cut into blocks of kSelBlock positions, one workgroup each:
+//     pool the block's importance scores (halo from the neighbours), write the pooled scores,
+//     histogram their leading 11 key bits, write the block's histogram;
+//   select_rank_kernel: one workgroup per segment adds the block histograms, picks the digit that
+//     holds the k-th largest score, collects that digit's scores in LDS and narrows them down to
+//     the exact k-th largest value tau and the number of scores equal to tau that belong to the
+//     top k (ties go to lower positions); then one ordered compaction of the positions with
+//     score > tau, or == tau among the first `need_eq`.
+// (One kernel with a per-segment ticket, the last block doing the ranking, was measured and
+// dropped: with 1024-thread workgroups at one per CU, the blocks of later segments queue behind
+// ranking workgroups and start tens of microseconds late.)
+// Keys are the bit patterns of the pooled scores (>= 0, so monotone).  While ranking, a wave owns
+// 2048 consecutive positions of a round, lane l the positions 64*j + l (j < 32): ballots are in
 // position order, so the ordered compaction needs no scan beyond the 16 wave totals.
-constexpr int kInlineGatherRows = 256;    // segments up to this many kept rows are gathered by select_kernel
+constexpr int kInlineGatherRows = 256;    // segments up to this many kept rows are gathered by the selection kernel
 
 struct GatherArgs {
   const unsigned char* k;
@@ -609,7 +611,6 @@ constexpr int kSelRankMax = 256;          // lists up to this length are ranked 
 constexpr int kSelCandidates = 12288;     // scores of one first-level digit that the LDS list can hold
 constexpr int kDigitShift = 20;           // first-level digit = key >> 20: sign (0), 8 exponent and 3 mantissa bits
 constexpr uint32_t kKeyNone = 0xffffffffu;
-static_assert(kSelBlock + 2 * kSelHaloMax <= kSelCandidates, "the importance staging of phase A lives in the candidate list");
 static_assert(kTicketBytes == SLKV_WORKSPACE_HEADER_BYTES, "the header documents the size of the ticket area");
 static_assert((0x7f800000u >> kDigitShift) < (uint32_t)kHistBins, "every key has a first-level digit inside the histogram");
 
@@ -625,11 +626,63 @@ __device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
 }
 
 template <int RADIUS, class TAB>   // pooling radius known at compile time (0..3), or -1: any radius
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
-                                                             const float* __restrict__ imp, float* __restrict__ pooled,
-                                                             uint32_t* __restrict__ blockhist, uint32_t* __restrict__ tickets,
-                                                             int32_t* __restrict__ kept_idx, int64_t* __restrict__ d_out_offsets,
-                                                             const GatherArgs ga) {
+__global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
+                                                                  const float* __restrict__ imp, float* __restrict__ pooled,
+                                                                  uint32_t* __restrict__ blockhist) {
+  constexpr int NT = kSelThreads;
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ float stage[kSelBlock + 2 * kSelHaloMax];
+  const int tid = threadIdx.x;
+  const int bid = blockIdx.x;
+  const int seg = find_segment(tab.blk_begin, tab.nseg, bid);
+  const int blk = bid - tab.blk_begin[seg];
+  const int n = tab.n[seg];
+  const int kk = tab.kkeep[seg];
+  const int m = n - w;
+  if (!(kk > 0 && kk < m)) return;                    // not ranked: nothing to pool (such segments have no block)
+  SLKV_STAMP(bid, 0);
+  const float* I = imp + tab.score_off[seg];
+  float* P = pooled + tab.score_off[seg];
+  const int radius = RADIUS >= 0 ? RADIUS : pool_kernel / 2;
+  const bool is_max = pool_mode != SLKV_POOL_AVG;
+  const float fill = is_max ? -INFINITY : 0.f;
+  const float inv_p = 1.f / (float)pool_kernel;
+  const int p0 = blk * kSelBlock;
+  const int cnt = min(kSelBlock, m - p0);
+  for (int s = tid; s < cnt + 2 * radius; s += NT) {   // stage[s] = importance at position p0 - radius + s
+    const int j = p0 - radius + s;
+    stage[s] = (j >= 0 && j < m) ? I[j] : fill;
+  }
+  for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < kSelBlock / NT; ++e) {
+    const int s = e * NT + tid;
+    if (s < cnt) {
+      float a = stage[s];
+      if (RADIUS >= 0) {
+#pragma unroll
+        for (int t = 1; t <= 2 * (RADIUS >= 0 ? RADIUS : 0); ++t) a = is_max ? fmaxf(a, stage[s + t]) : a + stage[s + t];
+      } else {
+        for (int t = 1; t <= 2 * radius; ++t) a = is_max ? fmaxf(a, stage[s + t]) : a + stage[s + t];
+      }
+      if (!is_max) a *= inv_p;
+      P[p0 + s] = a;
+      atomicAdd(&hist[score_key(a) >> kDigitShift], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* bh = blockhist + (size_t)(tab.hblk[seg] + blk) * kHistBins;
+  for (int i = tid; i < kHistBins; i += NT) bh[i] = hist[i];
+  SLKV_STAMP(bid, 1);
+}
+
+// Phase B: one workgroup per segment (unranked segments only write their positions).
+template <class TAB>
+__global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab, int w, const float* __restrict__ pooled,
+                                                                  const uint32_t* __restrict__ blockhist,
+                                                                  int32_t* __restrict__ kept_idx, int64_t* __restrict__ d_out_offsets,
+                                                                  const GatherArgs ga) {
   constexpr int NT = kSelThreads, NW = kSelWaves, EPT = kSelEPT, ROUND = kSelRound;
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t cand[kSelCandidates];
@@ -640,9 +693,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
   __shared__ uint32_t res[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int bid = blockIdx.x;
-  const int seg = find_segment(tab.blk_begin, tab.nseg, bid);
-  const int blk = bid - tab.blk_begin[seg];
+  const int seg = blockIdx.x;
+  const int bid = seg;
   const int nblk = tab.blk_begin[seg + 1] - tab.blk_begin[seg];
   const int n = tab.n[seg];
   const int kk = tab.kkeep[seg];
@@ -650,7 +702,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
   const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
   const bool small_seg = kept <= kInlineGatherRows;
   int32_t* out = kept_idx + tab.out_off[seg];
-  if (d_out_offsets && blk == 0 && tid == 0) {
+  if (d_out_offsets && tid == 0) {
     d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
     if (seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
   }
@@ -660,73 +712,31 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
       if (small_seg) sh_pos[pos] = j;
     }
   };
-  SLKV_STAMP(bid, 0);
+  SLKV_STAMP(bid, 2);
   if (small_seg)
     for (int i = tid; i < kInlineGatherRows; i += NT) sh_pos[i] = 0;
   __syncthreads();
   const bool ranked = kk > 0 && kk < m;
   if (!ranked) {
-    // one block: the whole segment, or only its window (plus the whole history when kk >= m)
     if (kk < 0) {
       for (int j = tid; j < n; j += NT) emit(j, j);
     } else {
-      const int hk = kk >= m ? m : 0;
-      for (int j = tid; j < hk; j += NT) emit(j, j);
-      for (int j = tid; j < w; j += NT) emit(hk + j, m + j);
+      for (int j = tid; j < w; j += NT) emit(j, m + j);   // kk == 0: the window alone
     }
   } else {
-    const float* I = imp + tab.score_off[seg];
-    float* P = pooled + tab.score_off[seg];
-    // ---------------- phase A: this block's pooled scores and their first-level histogram
+    const float* P = pooled + tab.score_off[seg];
     {
-      const int radius = RADIUS >= 0 ? RADIUS : pool_kernel / 2;
-      const bool is_max = pool_mode != SLKV_POOL_AVG;
-      const float fill = is_max ? -INFINITY : 0.f;
-      const float inv_p = 1.f / (float)pool_kernel;
-      const int p0 = blk * kSelBlock;
-      const int cnt = min(kSelBlock, m - p0);
-      float* stage = reinterpret_cast<float*>(cand);      // stage[s] = importance at position p0 - radius + s
-      for (int s = tid; s < cnt + 2 * radius; s += NT) {
-        const int j = p0 - radius + s;
-        stage[s] = (j >= 0 && j < m) ? I[j] : fill;
-      }
-      for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < kSelBlock / NT; ++e) {
-        const int s = e * NT + tid;
-        if (s < cnt) {
-          float a = stage[s];
-          if (RADIUS >= 0) {
-#pragma unroll
-            for (int t = 1; t <= 2 * (RADIUS >= 0 ? RADIUS : 0); ++t) a = is_max ? fmaxf(a, stage[s + t]) : a + stage[s + t];
-          } else {
-            for (int t = 1; t <= 2 * radius; ++t) a = is_max ? fmaxf(a, stage[s + t]) : a + stage[s + t];
-          }
-          if (!is_max) a *= inv_p;
-          st_dev(P + p0 + s, a);
-          atomicAdd(&hist[score_key(a) >> kDigitShift], 1u);
-        }
-      }
-      __syncthreads();
-    }
-    SLKV_STAMP(bid, 1);
-    if (nblk > 1) {
-      // publish the block histogram; the block that arrives last at the ticket adds them up
-      uint32_t* bh = blockhist + (size_t)(tab.hblk[seg] + blk) * kHistBins;
-      for (int i = tid; i < kHistBins; i += NT) st_dev(bh + i, hist[i]);
-      if (!last_arrival(tickets + kTicketSelect + tab.tick[seg], (uint32_t)nblk, &res[0])) return;
-      SLKV_STAMP(bid, 2);
-      const uint32_t* bh0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+      // first-level histogram of the segment: the sum of its blocks' histograms
       static_assert(kHistBins == 2 * NT, "a thread adds up two bins");
+      const uint32_t* bh0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
       uint32_t a0 = 0, a1 = 0;
       for (int b0 = 0; b0 < nblk; b0 += 8) {              // 16 loads in flight
         uint32_t v0[8], v1[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const int b = min(b0 + u, nblk - 1);
-          v0[u] = ld_dev(bh0 + (size_t)b * kHistBins + tid);
-          v1[u] = ld_dev(bh0 + (size_t)b * kHistBins + NT + tid);
+          v0[u] = bh0[(size_t)b * kHistBins + tid];
+          v1[u] = bh0[(size_t)b * kHistBins + NT + tid];
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -738,11 +748,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
       hist[tid] = a0;
       hist[NT + tid] = a1;
       __syncthreads();
-    } else {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this block's pooled scores are re-read below
-      __syncthreads();
     }
-
     SLKV_STAMP(bid, 3);
     // ---------------- phase B: the k-th largest pooled score of the segment
     const int rounds = (m + ROUND - 1) / ROUND;
@@ -752,7 +758,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const TAB tab, int 
       const int base = r * ROUND + wv * (64 * EPT) + lane;
       float ld[EPT];
 #pragma unroll
-      for (int j = 0; j < EPT; ++j) ld[j] = ld_dev(P + min(base + j * 64, m - 1));
+      for (int j = 0; j < EPT; ++j) ld[j] = P[min(base + j * 64, m - 1)];
 #pragma unroll
       for (int j = 0; j < EPT; ++j) key[j] = base + j * 64 < m ? score_key(ld[j]) : kKeyNone;
     };
@@ -1237,7 +1243,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const Gather
   const int64_t row = row0 + rel;
   if (row >= row1) return;
   const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
-  if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by select_kernel
+  if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by the selection kernel
   // (a position outside the segment cannot come out of the selection; clamped all the same, so
   // that no input can turn into an out-of-bounds read here)
   const int64_t tok = (int64_t)tab.tok_begin[seg] + min(max(kept_idx[row], 0), max(tab.n[seg] - 1, 0));
@@ -1295,7 +1301,7 @@ struct Geometry {
 
 struct Plan {
   int R, Rpad, CH;
-  int64_t hist_blocks;   // block histograms (segments of several selection blocks)
+  int64_t hist_blocks;   // block histograms of the selection
   int64_t ticketed;      // segments that need a ticket slot
   size_t part_bytes, lse_bytes, score_bytes, hist_bytes, table_bytes;
   size_t off_part, off_lse, off_imp, off_pooled, off_hist, off_table, total_bytes;
@@ -1304,7 +1310,7 @@ struct Plan {
 static bool seg_ranked(int64_t n, int64_t w, int64_t cap) { return n > w && n > cap && cap > w; }
 // key chunks of the scoring passes and blocks of the selection for one segment
 static int64_t seg_chunks(const Seg& s, int w, int64_t ch) { return seg_ranked(s.n, w, s.cap) ? (s.n - w + ch - 1) / ch : 0; }
-static int64_t seg_blocks(const Seg& s, int w) { return seg_ranked(s.n, w, s.cap) ? (s.n - w + kSelBlock - 1) / kSelBlock : 1; }
+static int64_t seg_blocks(const Seg& s, int w) { return seg_ranked(s.n, w, s.cap) ? (s.n - w + kSelBlock - 1) / kSelBlock : 0; }
 
 static void make_plan(const Geometry& g, Plan& p) {
   p.R = (g.Hq / g.Hkv) * g.w;
@@ -1328,8 +1334,8 @@ static void make_plan(const Geometry& g, Plan& p) {
   for (const Seg& s : g.segs) {
     const int64_t nc = seg_chunks(s, g.w, ch), nb = seg_blocks(s, g.w);
     chunks += nc;
-    if (nb > 1) p.hist_blocks += nb;
-    if (nc > 1 || nb > 1) p.ticketed += 1;
+    p.hist_blocks += nb;
+    if (nc > 1) p.ticketed += 1;
   }
   auto align = [](size_t x) { return (x + 255) / 256 * 256; };
   p.part_bytes = align((size_t)std::max<int64_t>(chunks, 1) * p.Rpad * sizeof(float));
@@ -1433,22 +1439,26 @@ static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, con
 }
 
 template <class TAB>
-static void launch_select(int blocks, hipStream_t st, const TAB& tab, const Geometry& g, const float* imp, float* pooled,
-                          uint32_t* blockhist, uint32_t* tickets, int32_t* kept_idx, int64_t* d_out_offsets,
+static void launch_select(int nseg, int blocks, hipStream_t st, const TAB& tab, const Geometry& g, const float* imp,
+                          float* pooled, uint32_t* blockhist, int32_t* kept_idx, int64_t* d_out_offsets,
                           const GatherArgs& ga) {
   const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
   const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
-#define SLKV_SELECT_LAUNCH(RAD)                                                                                        \
-  SLKV_LAUNCH((select_kernel<RAD, TAB>), dim3(blocks), dim3(kSelThreads), 0, st, tab, g.w, pool_kernel, g.pool, imp, \
-                     pooled, blockhist, tickets, kept_idx, d_out_offsets, ga)
-  switch (radius) {
-    case 0: SLKV_SELECT_LAUNCH(0); break;
-    case 1: SLKV_SELECT_LAUNCH(1); break;
-    case 2: SLKV_SELECT_LAUNCH(2); break;
-    case 3: SLKV_SELECT_LAUNCH(3); break;
-    default: SLKV_SELECT_LAUNCH(-1); break;
+#define SLKV_POOL_LAUNCH(RAD)                                                                                          \
+  SLKV_LAUNCH((select_pool_kernel<RAD, TAB>), dim3(blocks), dim3(kSelThreads), 0, st, tab, g.w, pool_kernel, g.pool, imp, \
+              pooled, blockhist)
+  if (blocks > 0) {
+    switch (radius) {
+      case 0: SLKV_POOL_LAUNCH(0); break;
+      case 1: SLKV_POOL_LAUNCH(1); break;
+      case 2: SLKV_POOL_LAUNCH(2); break;
+      case 3: SLKV_POOL_LAUNCH(3); break;
+      default: SLKV_POOL_LAUNCH(-1); break;
+    }
   }
-#undef SLKV_SELECT_LAUNCH
+#undef SLKV_POOL_LAUNCH
+  SLKV_LAUNCH(select_rank_kernel<TAB>, dim3(nseg), dim3(kSelThreads), 0, st, tab, g.w, (const float*)pooled,
+              (const uint32_t*)blockhist, kept_idx, d_out_offsets, ga);
 }
 
 // select_resident_kernel needs more LDS than a kernel gets by default: the limit is raised once per
@@ -1539,7 +1549,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
   Plan p;
   make_plan(g, p);
   if (p.ticketed > kTicketSlots)
-    return fail(SLKV_ERR_UNSUPPORTED, "%lld segments span several key chunks or selection blocks (limit %d)",
+    return fail(SLKV_ERR_UNSUPPORTED, "%lld segments span several key chunks (limit %d)",
                 (long long)p.ticketed, kTicketSlots);
   if (workspace_bytes < p.total_bytes)
     return fail(SLKV_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, p.total_bytes);
@@ -1597,7 +1607,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
         hipError_t se = launch_select_resident(nseg, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets, ga);
         if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
       } else {
-        launch_select(blocks, st, tab, g, imp, pooled, blockhist, tickets, d_kept_idx, d_out_offsets, ga);
+        launch_select(nseg, blocks, st, tab, g, imp, pooled, blockhist, d_kept_idx, d_out_offsets, ga);
       }
     }
     if (any_large) {
@@ -1660,8 +1670,8 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
       tab.tick[i] = (int32_t)tick_run;
       chunks += nc;
       blocks += nb;
-      if (nb > 1) hist_run += nb;
-      if (nc > 1 || nb > 1) tick_run += 1;
+      hist_run += nb;
+      if (nc > 1) tick_run += 1;
     }
     if (chunks >= (int64_t(1) << 31) || blocks >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "too many key chunks");
     // the remaining entries repeat the end values so that searches stay inside the table
