@@ -31,4 +31,5 @@ from .compress import (  # noqa: F401
     kept_count,
 )
 from .budgets import allocate_budgets, allocate_budgets_literal, allocate_budgets_per_query_head, fixed_from_beta  # noqa: F401
-from .behavior import row_weights, finalize_scores, harmonic, score_heads, score_heads_modes  # noqa: F401
+from .behavior import (row_weights, finalize_scores, harmonic, score_heads, score_heads_modes,  # noqa: F401
+                       attention_rows, score_heads_from_qk)

@@ -124,3 +124,30 @@ def score_heads_modes(rows, needle_start, needle_len, topk, aggregation="micro",
                 lg = acc[l, h, 6] / cnt if cnt > 0 else 0.0
                 scores[l, h] = (sf, lg, harmonic(sf, lg))
     return acc, scores
+
+
+def attention_rows(q, k):
+    """Attention-weight rows of Section 3.1 (Eq. 2-4) for decode queries against a fixed context.
+
+    q: [L, Hq, T, d] queries of T decode steps (fp32, or uint16 bfloat16 bit patterns);
+    k: [L, Hkv, n, d] keys of the context; the Hq / Hkv query heads of a group share a KV head.
+    Returns float64 rows [L, Hq, T, n]: softmax over the n keys of q . k / sqrt(d)."""
+    from .compress import bf16_bits_to_f64
+    q64, k64 = bf16_bits_to_f64(q), bf16_bits_to_f64(k)
+    L, Hq, T, d = q64.shape
+    Hkv, n = k64.shape[1], k64.shape[2]
+    G = Hq // Hkv
+    rows = np.empty((L, Hq, T, n), dtype=np.float64)
+    for l in range(L):
+        for h in range(Hq):
+            s = (q64[l, h] @ k64[l, h // G].T) / np.sqrt(float(d))     # Eq. (3)
+            s = s - s.max(axis=1, keepdims=True)
+            e = np.exp(s)
+            rows[l, h] = e / e.sum(axis=1, keepdims=True)                # Eq. (4)
+    return rows
+
+
+def score_heads_from_qk(q, k, needle_start, needle_len, topk, acc=None):
+    """Stage 1 when the attention rows are not given but implied by queries and keys: the rows
+    of attention_rows() go through Algorithm 1 exactly as in score_heads (float64 throughout)."""
+    return score_heads(attention_rows(q, k), needle_start, needle_len, topk, acc)

@@ -279,3 +279,45 @@ def config4(L=32, H=32, T=16, n=16384, needle_len=32, vocab=128000, seed_extra=0
         e = np.exp(z64)
         rows[l] = (e / e.sum(axis=-1, keepdims=True)).astype(np.float32)
     return NeedleRows(rows, start, needle_len, needle_len, token_ids)
+
+
+@dataclass
+class NeedleQK:
+    """Decode queries q [L, Hq, T, d] and context keys k [L, Hkv, n, d] (uint16 bfloat16 bit
+    patterns) of a needle-in-a-haystack run; the needle occupies [needle_start, +needle_len)."""
+    q: np.ndarray
+    k: np.ndarray
+    needle_start: int
+    needle_len: int
+    topk: int
+
+
+def config4_qk(L=32, Hq=32, Hkv=8, T=16, n=16384, d=128, needle_len=32, seed_extra=0, tie_rows=0):
+    """The queries and keys behind rows like those of config4(): K ~ N(0,1); a query is N(0,1),
+    and with probability 0.005 ("surface") it is pulled towards the key of the needle token being
+    emitted (start + t), with probability 0.015 ("logic") towards the mean of 8 keys drawn from
+    the needle's other tokens and the 16 tokens on either side; the pull is 12 (6) times the unit
+    key direction times sqrt(d), which raises those logits by about 12 (6 x the overlap).
+    tie_rows > 0: the first `tie_rows` KV heads of layer 0 get identical keys everywhere (every
+    logit of their rows ties)."""
+    rng = _rng(BASE_SEED + 4, 77, seed_extra)
+    G = Hq // Hkv
+    start = int(rng.integers(0, n - needle_len + 1))
+    k = rng.standard_normal((L, Hkv, n, d), dtype=np.float32)
+    for h in range(min(tie_rows, Hkv)):
+        k[0, h, :, :] = k[0, h, :1, :]
+    q = rng.standard_normal((L, Hq, T, d), dtype=np.float32)
+    kind = rng.random((L, Hq, T))
+    scale = np.float32(np.sqrt(d))
+    for l, h, t in zip(*np.nonzero(kind < 0.020)):
+        kv = h // G
+        if kind[l, h, t] < 0.005:
+            tgt = k[l, kv, start + (t % needle_len)]
+            q[l, h, t] += np.float32(12.0) * scale * tgt / np.linalg.norm(tgt) ** 2
+        else:
+            lo, hi = max(0, start - 16), min(n, start + needle_len + 16)
+            cand = np.array([p for p in range(lo, hi) if p != start + (t % needle_len)])
+            pos = rng.choice(cand, size=min(8, cand.shape[0]), replace=False)
+            tgt = k[l, kv, pos].mean(axis=0)
+            q[l, h, t] += np.float32(6.0) * scale * tgt / np.linalg.norm(tgt) ** 2
+    return NeedleQK(to_bf16_bits(q), to_bf16_bits(k), start, needle_len, needle_len)
