@@ -354,6 +354,27 @@ def main():
                          "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del rows
 
+    # Stage 1 straight from decode queries and context keys (same shape; the attention rows are never in memory)
+    if not args.no_stage1:
+        x = wl.config4_qk()
+        q4, k4 = api.to_device(x.q, "bf16"), api.to_device(x.k, "bf16")
+        acc4, _ = api.score_heads_qk(q4, k4, x.needle_start, x.needle_len, x.topk)
+        torch.cuda.synchronize()
+        reps = 5
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            api.score_heads_qk(q4, k4, x.needle_start, x.needle_len, x.topk, acc4)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        kbytes = k4.numel() * 2
+        out["stage1_from_qk"] = {"workload": "the same 32x32 heads x 16 decode rows over 16384 keys, rows computed on chip from bf16 Q and K",
+                                 "ms_per_call": round(ms, 4), "rows_per_s": round(32 * 32 * 16 / (ms * 1e-3), 1),
+                                 "key_bytes": kbytes, "key_GBs": round(kbytes / (ms * 1e-3) / 1e9, 1),
+                                 "hbm_frac_keys_once": round(kbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del q4, k4, x
+
     # CPU baseline: the float64 oracle, as it stands, on a bounded sample of the same workload,
     # also used as the parity check of what the GPU just produced.
     if not args.no_cpu:

@@ -108,6 +108,27 @@ slkv_status slkv_score_heads_ex(const slkv_score_params* params, const float* d_
                                 double* d_acc, double* d_scores,
                                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Stage 1 without attention rows in memory (Section 3.1, Eq. 2-4, feeding Algorithm 1): the row of
+ * query head hq at decode step t is softmax_j(q[l][hq][t] . k[l][hq / (Hq/Hkv)][j] / sqrt(d)) over the
+ * n context keys; the kernels compute the logits, the top-K set and the weight cells of every row
+ * on chip and add them into d_acc exactly as slkv_score_heads does.  Logits are fp32 sums of exact
+ * bf16 products, weights fp32 exponentials of them, so the cells agree with float64 arithmetic on
+ * the same inputs to about 1e-5 relative; two logits that differ by less than fp32 rounding may
+ * swap places in the top-K set.
+ *
+ * d_q   [L][Hq][T][d] bf16 queries of the T decode steps (device, read only)
+ * d_k   [L][Hkv][n][d] bf16 context keys (device, read only); Hq % Hkv == 0, d in {64, 128},
+ *       n*d*2 < 2^31; topk <= 64 (larger K: materialise the rows and call slkv_score_heads)
+ * d_acc [L][Hq][5], d_scores [L][Hq][3] (may be NULL): as in slkv_score_heads
+ * Errors: NULL, BAD_ARG, UNSUPPORTED (d, topk, size), WORKSPACE, HIP.
+ */
+slkv_status slkv_score_heads_qk(const void* d_q, const void* d_k, int32_t L, int32_t Hq, int32_t Hkv,
+                                int32_t T, int64_t n, int32_t d,
+                                int64_t needle_start, int32_t needle_len, int32_t topk,
+                                double* d_acc, double* d_scores,
+                                void* d_workspace, size_t workspace_bytes, void* hip_stream);
+size_t slkv_score_heads_qk_workspace_bytes(int32_t L, int32_t Hq, int32_t T, int64_t n);
+
 /* ------------------------------------------------------------------ Stage 2a ----------
  * Eq. (6) / Algorithm 2.  Pure host code, no GPU call.
  *
@@ -278,7 +299,9 @@ typedef enum {
   SLKV_K_SELECT = 3,        /* pooling + top-k */
   SLKV_K_GATHER = 4,        /* K/V row gather */
   SLKV_K_ROW_CELLS = 5,     /* Stage 1: per-row weight cells */
-  SLKV_K_HEAD_REDUCE = 6    /* Stage 1: per-head sums and scores */
+  SLKV_K_HEAD_REDUCE = 6,   /* Stage 1: per-head sums and scores */
+  SLKV_K_QK_CELLS = 7,      /* Stage 1 from queries and keys: logits, top-K and cells of every row */
+  SLKV_K_QK_FALLBACK = 8    /* the same for rows whose candidate list overflowed */
 } slkv_kernel_id;
 typedef struct {
   int32_t kernel; /* slkv_kernel_id */

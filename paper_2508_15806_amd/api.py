@@ -100,3 +100,15 @@ def score_heads_ex(rows, needle_start, needle_len, topk, aggregation=B.SLKV_AGG_
     ws = torch.empty((max(B.slkv_score_heads_workspace_bytes(L, H, T, n), 16),), dtype=torch.uint8, device=rows.device)
     B.slkv_score_heads_ex(rows, needle_start, needle_len, topk, acc, scores, ws, aggregation, components, stream)
     return acc, scores
+
+
+def score_heads_qk(q, k, needle_start, needle_len, topk, acc=None, stream=None):
+    """q [L,Hq,T,d], k [L,Hkv,n,d] bf16 device tensors.  Returns (acc [L,Hq,5], scores [L,Hq,3]) float64 device tensors."""
+    L, Hq, T, d = q.shape
+    n = k.shape[2]
+    if acc is None:
+        acc = torch.zeros((L, Hq, 5), dtype=torch.float64, device=q.device)
+    scores = torch.empty((L, Hq, 3), dtype=torch.float64, device=q.device)
+    ws = torch.empty((B.slkv_score_heads_qk_workspace_bytes(L, Hq, T, n),), dtype=torch.uint8, device=q.device)
+    B.slkv_score_heads_qk(q, k, needle_start, needle_len, topk, acc, scores, ws, stream)
+    return acc, scores

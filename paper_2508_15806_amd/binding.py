@@ -22,13 +22,15 @@ SLKV_AGG_MICRO, SLKV_AGG_MACRO = 0, 1
 STATUS_NAMES = {0: "SLKV_OK", 1: "SLKV_ERR_NULL", 2: "SLKV_ERR_BAD_ARG", 3: "SLKV_ERR_BAD_VALUE",
                 4: "SLKV_ERR_UNSUPPORTED", 5: "SLKV_ERR_WORKSPACE", 6: "SLKV_ERR_CAPACITY", 7: "SLKV_ERR_HIP"}
 
-EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads", "slkv_score_heads_ex",
+EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads", "slkv_score_heads_ex", "slkv_score_heads_qk",
+           "slkv_score_heads_qk_workspace_bytes",
            "slkv_score_heads_workspace_bytes", "slkv_allocate_budgets", "slkv_fixed_from_beta",
            "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer", "slkv_compress_layer_static",
            "slkv_recompress_sizes", "slkv_recompress_workspace_bytes", "slkv_recompress_layer",
            "slkv_profile_begin", "slkv_profile_end"]
 
-KERNEL_NAMES = ["score_stats", "combine", "score_accum", "select", "gather", "row_cells", "head_reduce"]
+KERNEL_NAMES = ["score_stats", "combine", "score_accum", "select", "gather", "row_cells", "head_reduce", "qk_cells",
+                "qk_fallback"]
 
 
 class SlkvError(RuntimeError):
@@ -111,6 +113,12 @@ def lib():
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.slkv_score_heads_ex.restype = C.c_int
         L.slkv_score_heads_ex.argtypes = [C.POINTER(ScoreParams)] + L.slkv_score_heads.argtypes
+        L.slkv_score_heads_qk_workspace_bytes.restype = C.c_size_t
+        L.slkv_score_heads_qk_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64]
+        L.slkv_score_heads_qk.restype = C.c_int
+        L.slkv_score_heads_qk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                          C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
         L.slkv_profile_begin.restype = C.c_int
         L.slkv_profile_begin.argtypes = [C.c_int32]
         L.slkv_profile_end.restype = C.c_int
@@ -251,6 +259,19 @@ def slkv_score_heads_ex(rows, needle_start, needle_len, topk, acc, scores, works
     prm = ScoreParams(C.sizeof(ScoreParams), int(aggregation), int(bool(components[0])), int(bool(components[1])),
                       int(bool(components[2])), 0)
     _check(lib().slkv_score_heads_ex(C.byref(prm), _ptr(rows), L, H, T, n, int(needle_start), int(needle_len), int(topk),
+                                     _ptr(acc), _ptr(scores), _ptr(workspace),
+                                     int(workspace.numel() * workspace.element_size()), _stream(stream)))
+
+
+def slkv_score_heads_qk_workspace_bytes(L, Hq, T, n):
+    return int(lib().slkv_score_heads_qk_workspace_bytes(L, Hq, T, n))
+
+
+def slkv_score_heads_qk(q, k, needle_start, needle_len, topk, acc, scores, workspace, stream=None):
+    """q: [L, Hq, T, d], k: [L, Hkv, n, d] bf16 device tensors; acc [L, Hq, 5] float64 (in/out); scores [L, Hq, 3] or None."""
+    L, Hq, T, d = q.shape
+    Hkv, n = k.shape[1], k.shape[2]
+    _check(lib().slkv_score_heads_qk(_ptr(q), _ptr(k), L, Hq, Hkv, T, n, d, int(needle_start), int(needle_len), int(topk),
                                      _ptr(acc), _ptr(scores), _ptr(workspace),
                                      int(workspace.numel() * workspace.element_size()), _stream(stream)))
 

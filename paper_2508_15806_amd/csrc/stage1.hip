@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "device_utils.h"
 #include "launch.h"
@@ -20,9 +21,8 @@ constexpr int kS1Cand = 512;      // weights at or above the bound that the exac
 // the row from memory in every sweep.
 // cells[row] = (WO, WD, WS, Wide).
 template <bool RESIDENT>
-__global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* __restrict__ rows, int32_t n,
-                                                                  int32_t needle_start, int32_t needle_len, int32_t topk,
-                                                               double* __restrict__ cells) {
+__device__ __forceinline__ void row_cells_impl(const float* __restrict__ W, int32_t n, int32_t needle_start,
+                                               int32_t needle_len, int32_t topk, double* __restrict__ c_out) {
   constexpr int NT = kS1Threads;
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t sh_scan[NT / 64];
@@ -31,7 +31,6 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
   __shared__ uint32_t sh_u[NT / 64];
 
   const int tid = threadIdx.x;
-  const float* W = rows + (int64_t)blockIdx.x * n;
   const int32_t ne = needle_start + needle_len;
 
   // sweep helper of the general path: f(position, value) over the row, re-read from memory
@@ -202,7 +201,7 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
       }
       if (tid == 0) {
         const double WS = fmax(0.0, tnw - wo);
-        double* c = cells + (int64_t)blockIdx.x * 4;
+        double* c = c_out;
         c[0] = wo;
         c[1] = wd;
         c[2] = WS;
@@ -303,12 +302,19 @@ __global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* _
     const double WO = wo + (double)tau_val * (double)take_needle;
     const double WD = wd + (double)tau_val * (double)(need_eq - take_needle);
     const double WS = fmax(0.0, tnw - WO);
-    double* c = cells + (int64_t)blockIdx.x * 4;
+    double* c = c_out;
     c[0] = WO;
     c[1] = WD;
     c[2] = WS;
     c[3] = tot - WO - WD - WS;
   }
+}
+
+template <bool RESIDENT>
+__global__ __launch_bounds__(kS1Threads, 4) void row_cells_kernel(const float* __restrict__ rows, int32_t n,
+                                                                  int32_t needle_start, int32_t needle_len, int32_t topk,
+                                                                  double* __restrict__ cells) {
+  row_cells_impl<RESIDENT>(rows + (int64_t)blockIdx.x * n, n, needle_start, needle_len, topk, cells + (int64_t)blockIdx.x * 4);
 }
 
 // Steps 5-7 of Algorithm 1 (0/0 = 0); a component that is switched off enters as 0.
@@ -359,6 +365,355 @@ __global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t hea
     scores[(int64_t)hd * 3 + 0] = SF;
     scores[(int64_t)hd * 3 + 1] = LG;
     scores[(int64_t)hd * 3 + 2] = INF;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage 1 straight from the decode queries and the context keys (Section 3.1, Eq. 2-4 feeding
+// Algorithm 1): the attention rows are never written anywhere.  One workgroup owns 64 query rows
+// of one KV head (the T decode steps of its G query heads) and all n keys.
+//
+// The keys are walked in super-chunks of kQkSuper keys, twice each (the second time they come
+// from cache): the first walk computes the logits with the 32x32x16 bf16 MFMA (a lane owns one
+// query row and 16 keys of a 32-key sub-tile) and updates, per lane, the running softmax
+// statistics, the needle mass and 16 running maxima; the maxima of the 4 lanes of a row are 64
+// maxima of disjoint key subsets, and their K-th largest is a lower bound of the row's K-th
+// largest logit.  The second walk computes the logits again and appends those at or above the
+// bound (a few dozen per row) to the row's candidate list in LDS; lists are re-filtered with the
+// tighter bound after every super-chunk.  At the end a wave per row ranks its candidates exactly
+// (larger logit first, equal logits by lower position), turns the K winners into weights with
+// the row's log-sum-exp and splits them into WO / WD by needle membership.  A row whose list
+// overflows (many equal logits at the top) is flagged and redone by qk_fallback_kernel.
+constexpr int kQkThreads = 256;
+constexpr int kQkRows = 64;
+constexpr int kQkTile = 64;
+constexpr int kQkCand = 128;
+constexpr int kQkSuper = 2048;
+constexpr int kQkFallbackWGs = 128;
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 qk_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float qk_f32x16;
+typedef uint32_t qk_u32x4 __attribute__((ext_vector_type(4)));
+union QkPack16 {
+  qk_u32x4 u;
+  qk_bf16x8 b;
+};
+
+template <int DK>
+struct QkLds {
+  static constexpr int ROWB = DK * 2 + 16;                 // padded key row: conflict-free 16-byte operand reads
+  unsigned char ktile[2][kQkTile * ROWB];
+  float cand_x[kQkRows][kQkCand];
+  int32_t cand_p[kQkRows][kQkCand];
+  float mx[kQkRows][64];                                    // subset maxima of a row: (ks, half, i)
+  float st_m[kQkRows][4], st_s[kQkRows][4], st_t[kQkRows][4];
+  float bound[kQkRows];
+  uint32_t cnt[kQkRows];
+  uint32_t ovf[kQkRows];
+};
+
+__device__ __forceinline__ float key_to_float(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
+
+template <int DK>
+__global__ __launch_bounds__(kQkThreads, 1) void qk_cells_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ kmat,
+                                                                 int Hq, int Hkv, int T, int n, int rowgroups,
+                                                                 int needle_start, int needle_len, int topk, float c_log2,
+                                                                 double* __restrict__ cells, unsigned char* __restrict__ overflow) {
+  constexpr int KK = DK / 16;
+  constexpr int ROWB = QkLds<DK>::ROWB;
+  constexpr int CPR = DK * 2 / 16;                  // 16-byte pieces per key row
+  constexpr int LPT = kQkTile * CPR / kQkThreads;   // pieces per thread per tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char qk_smem[];
+  QkLds<DK>& S = *reinterpret_cast<QkLds<DK>*>(qk_smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int rb = wv & 1, ks = wv >> 1, l32 = lane & 31, half = lane >> 5;
+  const int G = Hq / Hkv, R = G * T;
+  const int rg = blockIdx.x % rowgroups, seg = blockIdx.x / rowgroups;   // seg = l * Hkv + kvh
+  const int l = seg / Hkv, kvh = seg % Hkv;
+  const int row0 = rg * kQkRows;
+  const int nrows = min(kQkRows, R - row0);
+  const int64_t rowid0 = ((int64_t)l * Hq + (int64_t)kvh * G) * T + row0;   // first global row of this workgroup
+  const uint16_t* qbase = q + rowid0 * DK;
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(kmat + (int64_t)seg * n * DK);
+  const int r = rb * 32 + l32;                       // this lane's row inside the workgroup
+  const bool row_ok = r < nrows;
+  const int ne = needle_start + needle_len;
+
+  for (int i = tid; i < kQkRows; i += kQkThreads) {
+    S.cnt[i] = 0;
+    S.ovf[i] = 0;
+    S.bound[i] = INFINITY;
+  }
+  qk_bf16x8 qreg[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    QkPack16 p;
+    p.u = *reinterpret_cast<const qk_u32x4*>(qbase + (int64_t)min(r, nrows - 1) * DK + kk * 16 + half * 8);
+    qreg[kk] = p.b;
+  }
+  float m_run = -INFINITY, s_run = 0.f, t_run = 0.f;   // running maximum, sum of exp2(x - max), the same over the needle
+  float mxs[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) mxs[i] = -INFINITY;
+  float bound = INFINITY;
+
+  const uint32_t piece_off = (uint32_t)(tid % CPR) * 16u;
+  const int piece_row = tid / CPR;
+  qk_u32x4 pf0[LPT], pf1[LPT];
+  // tiles of 64 keys of [key_lo, key_hi): HBM / cache -> registers -> LDS, two tiles in flight
+  auto walk = [&](int key_lo, int key_hi, auto body) __attribute__((always_inline)) {
+    const int ntile = (((key_hi - key_lo + kQkTile - 1) / kQkTile) + 1) & ~1;   // even; a surplus tile is fully masked
+    auto issue = [&](int t, qk_u32x4 (&pf)[LPT]) __attribute__((always_inline)) {
+      const int key0 = key_lo + t * kQkTile + piece_row;
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) {
+        const int key = min(key0 + i * (kQkThreads / CPR), key_hi - 1);
+        pf[i] = *reinterpret_cast<const qk_u32x4*>(kbase + ((uint32_t)key * (uint32_t)(DK * 2) + piece_off));
+      }
+    };
+    auto tile = [&](int t, qk_u32x4 (&pf)[LPT]) __attribute__((always_inline)) {
+      const int buf = t & 1;
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) {
+        const int idx = i * kQkThreads + tid;
+        *reinterpret_cast<qk_u32x4*>(&S.ktile[buf][(idx / CPR) * ROWB + (idx % CPR) * 16]) = pf[i];
+      }
+      issue(t + 2, pf);
+      __syncthreads();
+      qk_f32x16 acc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        QkPack16 p;
+        p.u = *reinterpret_cast<const qk_u32x4*>(&S.ktile[buf][(ks * 32 + l32) * ROWB + kk * 32 + half * 16]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[kk], acc, 0, 0, 0);
+      }
+      // lane: row r, keys key0 + 8*(i/4) + 4*half + i%4
+      const int key0 = key_lo + t * kQkTile + ks * 32 + 4 * half;
+      float x[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) x[i] = key0 + 8 * (i >> 2) + (i & 3) < key_hi ? acc[i] * c_log2 : -INFINITY;
+      body(key0, x);
+    };
+    issue(0, pf0);
+    issue(1, pf1);
+    for (int t = 0; t < ntile; t += 2) {
+      tile(t, pf0);
+      tile(t + 1, pf1);
+    }
+    __syncthreads();                                  // the tile buffers are free again
+  };
+
+  for (int sc0 = 0; sc0 < n; sc0 += kQkSuper) {
+    const int sc1 = min(n, sc0 + kQkSuper);
+    // first walk: softmax statistics, needle mass, subset maxima
+    walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
+      float mx = x[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+      const float mn = fmaxf(m_run, mx);
+      const float mu = mn == -INFINITY ? 0.f : mn;
+      const float scale = __builtin_amdgcn_exp2f(m_run - mu);
+      float sum = 0.f, tsum = 0.f;
+      const bool near_needle = key0 + 32 > needle_start && key0 < ne;     // wave-uniform up to `half`
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float e = __builtin_amdgcn_exp2f(x[i] - mu);
+        sum += e;
+        if (near_needle) {
+          const int key = key0 + 8 * (i >> 2) + (i & 3);
+          tsum += (key >= needle_start && key < ne) ? e : 0.f;
+        }
+        mxs[i] = fmaxf(mxs[i], x[i]);
+      }
+      s_run = s_run * scale + sum;
+      t_run = t_run * scale + tsum;
+      m_run = mn;
+    });
+    // bound of every row: the K-th largest of its 64 subset maxima; candidate lists filtered by it
+#pragma unroll
+    for (int i = 0; i < 16; ++i) S.mx[r][(ks * 2 + half) * 16 + i] = mxs[i];
+    __syncthreads();
+    for (int rr = wv * 16; rr < wv * 16 + 16; ++rr) {
+      const uint32_t mkey = float_key(S.mx[rr][lane]);
+      uint32_t tkey = 0;
+#pragma unroll
+      for (int b = 31; b >= 0; --b) {
+        const uint32_t trial = tkey | (1u << b);
+        if ((uint32_t)__popcll(__ballot(mkey >= trial)) >= (uint32_t)topk) tkey = trial;
+      }
+      const float nb = rr < nrows ? key_to_float(tkey) : INFINITY;
+      const uint32_t c = S.cnt[rr];
+      if (c > (uint32_t)kQkCand) {                    // the list overflowed: the row goes to the fallback
+        if (lane == 0) {
+          S.ovf[rr] = 1;
+          S.cnt[rr] = 0;
+          S.bound[rr] = INFINITY;
+        }
+      } else {
+        const float x0 = lane < (int)c ? S.cand_x[rr][lane] : -INFINITY, x1 = lane + 64 < (int)c ? S.cand_x[rr][lane + 64] : -INFINITY;
+        const int32_t p0 = S.cand_p[rr][lane], p1 = S.cand_p[rr][lane + 64];
+        const bool k0 = lane < (int)c && x0 >= nb, k1 = lane + 64 < (int)c && x1 >= nb;
+        const unsigned long long m0 = __ballot(k0), m1 = __ballot(k1);
+        const uint32_t n0 = (uint32_t)__popcll(m0);
+        const uint32_t lb0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m0, 0u));
+        const uint32_t lb1 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, 0u));
+        if (k0) {
+          S.cand_x[rr][lb0] = x0;
+          S.cand_p[rr][lb0] = p0;
+        }
+        if (k1) {
+          S.cand_x[rr][n0 + lb1] = x1;
+          S.cand_p[rr][n0 + lb1] = p1;
+        }
+        if (lane == 0) {
+          S.cnt[rr] = n0 + (uint32_t)__popcll(m1);
+          if (!S.ovf[rr]) S.bound[rr] = nb;
+        }
+      }
+    }
+    __syncthreads();
+    bound = row_ok ? S.bound[r] : INFINITY;
+    // second walk: the logits at or above the bound join the row's list
+    walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (x[i] >= bound) {
+          const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
+          if (slot < (uint32_t)kQkCand) {
+            S.cand_x[r][slot] = x[i];
+            S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
+          }
+        }
+      }
+    });
+  }
+
+  // statistics of a row: its 4 lanes -> log-sum-exp and needle mass
+  S.st_m[r][ks * 2 + half] = m_run;
+  S.st_s[r][ks * 2 + half] = s_run;
+  S.st_t[r][ks * 2 + half] = t_run;
+  __syncthreads();
+  for (int rr = wv * 16; rr < min(wv * 16 + 16, nrows); ++rr) {
+    float M = S.st_m[rr][0];
+#pragma unroll
+    for (int j = 1; j < 4; ++j) M = fmaxf(M, S.st_m[rr][j]);
+    float ssum = 0.f, tsum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float f = __builtin_amdgcn_exp2f(S.st_m[rr][j] - M);
+      ssum += S.st_s[rr][j] * f;
+      tsum += S.st_t[rr][j] * f;
+    }
+    const float lse = M + log2f(ssum);
+    const double tnw = (double)tsum / (double)ssum;
+    const uint32_t c = S.cnt[rr];
+    const bool over = S.ovf[rr] || c > (uint32_t)kQkCand;
+    if (lane == 0) overflow[rowid0 + rr] = over ? 1 : 0;
+    if (over) continue;
+    // exact rank of the candidates: larger logit first, equal logits by lower position
+    const float x0 = lane < (int)c ? S.cand_x[rr][lane] : -INFINITY, x1 = lane + 64 < (int)c ? S.cand_x[rr][lane + 64] : -INFINITY;
+    const int32_t p0 = S.cand_p[rr][lane], p1 = S.cand_p[rr][lane + 64];
+    uint32_t a0 = 0, a1 = 0;
+    for (uint32_t j = 0; j < c; ++j) {
+      const float xj = S.cand_x[rr][j];
+      const int32_t pj = S.cand_p[rr][j];
+      a0 += (xj > x0 || (xj == x0 && pj < p0)) ? 1u : 0u;
+      a1 += (xj > x1 || (xj == x1 && pj < p1)) ? 1u : 0u;
+    }
+    double wo = 0.0, wd = 0.0;
+    if (lane < (int)c && a0 < (uint32_t)topk) {
+      const double wgt = (double)__builtin_amdgcn_exp2f(x0 - lse);
+      if (p0 >= needle_start && p0 < ne) wo += wgt; else wd += wgt;
+    }
+    if (lane + 64 < (int)c && a1 < (uint32_t)topk) {
+      const double wgt = (double)__builtin_amdgcn_exp2f(x1 - lse);
+      if (p1 >= needle_start && p1 < ne) wo += wgt; else wd += wgt;
+    }
+    wo = wave_sum<double>(wo);
+    wd = wave_sum<double>(wd);
+    if (lane == 0) {
+      const double WS = fmax(0.0, tnw - wo);
+      double* cdst = cells + (rowid0 + rr) * 4;
+      cdst[0] = wo;
+      cdst[1] = wd;
+      cdst[2] = WS;
+      cdst[3] = 1.0 - wo - wd - WS;                  // a softmax row sums to one
+    }
+  }
+}
+
+// Rows flagged by qk_cells_kernel: the row's weights are written to this workgroup's slot of the
+// workspace (plain dot products, softmax in three sweeps) and go through the general path of the
+// row kernel, which handles any number of equal weights.
+template <int DK>
+__global__ __launch_bounds__(kS1Threads) void qk_fallback_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ kmat,
+                                                                 int Hq, int Hkv, int T, int n, int64_t nrows_total,
+                                                                 int needle_start, int needle_len, int topk, float c_log2,
+                                                                 const unsigned char* __restrict__ overflow, float* __restrict__ slots,
+                                                                 double* __restrict__ cells) {
+  __shared__ float qs[DK];
+  __shared__ float red[kS1Threads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int G = Hq / Hkv;
+  float* W = slots + (int64_t)blockIdx.x * n;
+  auto block_max = [&](float v) {
+#pragma unroll
+    for (int dlt = 32; dlt > 0; dlt >>= 1) v = fmaxf(v, __shfl_xor(v, dlt, 64));
+    __syncthreads();
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float o = red[0];
+    for (int i = 1; i < kS1Threads / 64; ++i) o = fmaxf(o, red[i]);
+    return o;
+  };
+  auto block_add = [&](float v) {
+    v = wave_sum<float>(v);
+    __syncthreads();
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float o = red[0];
+    for (int i = 1; i < kS1Threads / 64; ++i) o += red[i];
+    return o;
+  };
+  for (int64_t row = blockIdx.x; row < nrows_total; row += gridDim.x) {
+    if (!overflow[row]) continue;                     // uniform over the workgroup
+    const int64_t hq_l = row / T;                     // l * Hq + hq
+    const int l = (int)(hq_l / Hq), hq = (int)(hq_l % Hq);
+    const uint16_t* kb = kmat + ((int64_t)l * Hkv + hq / G) * n * DK;
+    __syncthreads();
+    for (int p = tid; p < DK; p += kS1Threads) qs[p] = __uint_as_float((uint32_t)q[row * DK + p] << 16);
+    __syncthreads();
+    float mx = -INFINITY;
+    for (int j = tid; j < n; j += kS1Threads) {
+      float acc = 0.f;
+      for (int p = 0; p < DK; p += 2) {
+        const uint32_t pr = *reinterpret_cast<const uint32_t*>(kb + (int64_t)j * DK + p);
+        acc = fmaf(qs[p], __uint_as_float(pr << 16), acc);
+        acc = fmaf(qs[p + 1], __uint_as_float(pr & 0xffff0000u), acc);
+      }
+      const float x = acc * c_log2;
+      W[j] = x;
+      mx = fmaxf(mx, x);
+    }
+    mx = block_max(mx);
+    float sum = 0.f;
+    for (int j = tid; j < n; j += kS1Threads) {
+      const float e = __builtin_amdgcn_exp2f(W[j] - mx);
+      W[j] = e;
+      sum += e;
+    }
+    sum = block_add(sum);
+    const float inv = 1.f / sum;
+    for (int j = tid; j < n; j += kS1Threads) W[j] *= inv;
+    __threadfence_block();
+    __syncthreads();
+    row_cells_impl<false>(W, n, needle_start, needle_len, topk, cells + row * 4);
+    __syncthreads();
   }
 }
 
@@ -444,4 +799,113 @@ extern "C" slkv_status slkv_score_heads_ex(const slkv_score_params* params, cons
   if (params->reserved != 0) return fail(SLKV_ERR_BAD_ARG, "params.reserved must be 0");
   return run_score_heads(d_rows, L, H, T, n, needle_start, needle_len, topk, d_acc, d_scores, d_workspace, workspace_bytes,
                          hip_stream, params);
+}
+
+// ------------------------------------------------------------------ Stage 1 from queries and keys
+
+namespace {
+
+struct QkLayout {
+  size_t cells_bytes, flags_bytes, slots_bytes, off_flags, off_slots, total;
+};
+
+QkLayout qk_layout(int64_t rows, int64_t n) {
+  auto align = [](size_t x) { return (x + 255) / 256 * 256; };
+  QkLayout w;
+  w.cells_bytes = align((size_t)rows * 4 * sizeof(double));
+  w.flags_bytes = align((size_t)rows);
+  w.slots_bytes = align((size_t)kQkFallbackWGs * (size_t)n * sizeof(float));
+  w.off_flags = w.cells_bytes;
+  w.off_slots = w.off_flags + w.flags_bytes;
+  w.total = w.off_slots + w.slots_bytes;
+  return w;
+}
+
+// LDS above the default limit is requested once per kernel instance and device.
+template <int DK>
+hipError_t qk_prepare() {
+  static std::mutex mu;
+  static uint64_t done = 0;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lk(mu);
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t(1) << dev) : 0;
+  if (!(done & bit)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_cells_kernel<DK>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)sizeof(QkLds<DK>));
+    if (e != hipSuccess) return e;
+    done |= bit;
+  }
+  return hipSuccess;
+}
+
+template <int DK>
+slkv_status qk_launch(const uint16_t* q, const uint16_t* k, int32_t L, int32_t Hq, int32_t Hkv, int32_t T, int32_t n,
+                      int32_t needle_start, int32_t needle_len, int32_t topk, double* d_acc, double* d_scores,
+                      unsigned char* ws, const QkLayout& w, hipStream_t st) {
+  hipError_t pe = qk_prepare<DK>();
+  if (pe != hipSuccess) return fail(SLKV_ERR_HIP, "kernel set-up failed: %s", hipGetErrorString(pe));
+  const int G = Hq / Hkv, R = G * T, rowgroups = (R + kQkRows - 1) / kQkRows;
+  const int64_t rows = (int64_t)L * Hq * T;
+  double* cells = (double*)ws;
+  unsigned char* flags = ws + w.off_flags;
+  float* slots = (float*)(ws + w.off_slots);
+  const float c_log2 = (float)(1.4426950408889634 / std::sqrt((double)DK));
+  {
+    ScopedKernelTimer tm(SLKV_K_QK_CELLS, st);
+    SLKV_LAUNCH(qk_cells_kernel<DK>, dim3((unsigned)(L * Hkv * rowgroups)), dim3(kQkThreads), sizeof(QkLds<DK>), st, q, k, Hq, Hkv,
+                T, n, rowgroups, needle_start, needle_len, topk, c_log2, cells, flags);
+  }
+  {
+    ScopedKernelTimer tm(SLKV_K_QK_FALLBACK, st);
+    SLKV_LAUNCH(qk_fallback_kernel<DK>, dim3(kQkFallbackWGs), dim3(kS1Threads), 0, st, q, k, Hq, Hkv, T, n, rows, needle_start,
+                needle_len, topk, c_log2, (const unsigned char*)flags, slots, cells);
+  }
+  const int heads = L * Hq;
+  {
+    ScopedKernelTimer tm(SLKV_K_HEAD_REDUCE, st);
+    SLKV_LAUNCH(head_reduce_kernel<5>, dim3((heads + 127) / 128), dim3(128), 0, st, (const double*)cells, heads, T, d_acc,
+                d_scores, 0, 1, 1, 1);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+  return SLKV_OK;
+}
+
+}  // namespace
+
+extern "C" size_t slkv_score_heads_qk_workspace_bytes(int32_t L, int32_t Hq, int32_t T, int64_t n) {
+  if (L < 1 || Hq < 1 || T < 1 || n < 1) return 0;
+  return qk_layout((int64_t)L * Hq * T, n).total;
+}
+
+extern "C" slkv_status slkv_score_heads_qk(const void* d_q, const void* d_k, int32_t L, int32_t Hq, int32_t Hkv, int32_t T,
+                                           int64_t n, int32_t d, int64_t needle_start, int32_t needle_len, int32_t topk,
+                                           double* d_acc, double* d_scores, void* d_workspace, size_t workspace_bytes,
+                                           void* hip_stream) {
+  clear_error();
+  if (!d_q || !d_k || !d_acc || !d_workspace) return fail(SLKV_ERR_NULL, "d_q, d_k, d_acc and d_workspace are required");
+  if (L < 1 || Hq < 1 || Hkv < 1 || T < 1 || n < 1) return fail(SLKV_ERR_BAD_ARG, "L, Hq, Hkv, T, n must be >= 1");
+  if (Hq % Hkv) return fail(SLKV_ERR_BAD_ARG, "Hq %% Hkv != 0");
+  if (d != 64 && d != 128) return fail(SLKV_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", d);
+  if (n * d * 2 >= (int64_t(1) << 31)) return fail(SLKV_ERR_UNSUPPORTED, "one head's keys span 2 GiB or more");
+  const int64_t rows = (int64_t)L * Hq * T;
+  if (rows >= (int64_t(1) << 31) || (int64_t)L * Hkv * (((int64_t)(Hq / Hkv) * T + kQkRows - 1) / kQkRows) >= (int64_t(1) << 31))
+    return fail(SLKV_ERR_BAD_ARG, "too many rows");
+  if (needle_len < 1 || needle_start < 0 || needle_start + needle_len > n)
+    return fail(SLKV_ERR_BAD_ARG, "needle [%lld, +%d) outside [0, %lld)", (long long)needle_start, needle_len, (long long)n);
+  if (topk < 1 || topk > n) return fail(SLKV_ERR_BAD_ARG, "topk %d outside 1..n", topk);
+  if (topk > 64) return fail(SLKV_ERR_UNSUPPORTED, "topk %d > 64 (use slkv_score_heads on materialised rows)", topk);
+  const void* ptrs[] = {d_q, d_k, d_acc, d_scores, d_workspace};
+  for (const void* ptr : ptrs)
+    if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(SLKV_ERR_BAD_ARG, "device pointer %p not 16-byte aligned", ptr);
+  const QkLayout w = qk_layout(rows, n);
+  if (workspace_bytes < w.total) return fail(SLKV_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, w.total);
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (d == 128)
+    return qk_launch<128>((const uint16_t*)d_q, (const uint16_t*)d_k, L, Hq, Hkv, T, (int32_t)n, (int32_t)needle_start, needle_len,
+                          topk, d_acc, d_scores, (unsigned char*)d_workspace, w, st);
+  return qk_launch<64>((const uint16_t*)d_q, (const uint16_t*)d_k, L, Hq, Hkv, T, (int32_t)n, (int32_t)needle_start, needle_len, topk,
+                       d_acc, d_scores, (unsigned char*)d_workspace, w, st);
 }
