@@ -176,6 +176,10 @@ def main():
                                           "p10": round(float(np.percentile(lat, 10)), 5),
                                           "p90": round(float(np.percentile(lat, 90)), 5), "n": int(nlat)},
                   "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
+                  # the HBM-bound kernels against the chip peak: 4 B per ranked history key for the selection,
+                  # 1 KiB (K and V row, read + written) per kept row for the gather launch
+                  "select_GBs": round(4.0 * (n - w) * float(np.mean([x[3] for x in work])) / (kernel_ms.get("select", float("nan")) * 1e-3) / 1e9, 1),
+                  "gather_GBs": round(float(np.mean([x[2] for x in work if x[2] > 0])) * d * 2 * 2 * 2 / (kernel_ms.get("gather", float("nan")) * 1e-3) / 1e9, 1),
                   "kernel_launches_per_step": kernel_launches,
                   "kernel_sum_ms": round(sum(kernel_ms[k] * kernel_launches[k] for k in kernel_ms), 5)},
     }

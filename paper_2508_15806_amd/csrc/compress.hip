@@ -230,7 +230,11 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int key = min(key0 + i * (256 / CPR), key_end - 1);
-      pf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase + ((uint32_t)key * row_bytes + piece_off)));
+#ifndef SLKV_NT_MODE
+#define SLKV_NT_MODE 3
+#endif
+      const u32x4* src = reinterpret_cast<const u32x4*>(kbase + ((uint32_t)key * row_bytes + piece_off));
+      pf[i] = ((SLKV_NT_MODE >> (PASS - 1)) & 1) ? __builtin_nontemporal_load(src) : *src;
     }
   };
   auto store_tile = [&](const u32x4 (&pf)[LPT], int buf) __attribute__((always_inline)) {
@@ -380,7 +384,111 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   }
   using T = std::true_type;
   using F = std::false_type;
-  if (PASS == 1) {
+  // Pass 1 with both sub-tiles of a tile in one wave (RB == 4; up to 64 rows per wave): software pipeline over sub-tiles.
+  // The MFMAs of sub-tile s (two interleaved chains, one per row tile) are issued one per slot,
+  // each slot also carrying the exponentials of two logits of sub-tile s-1 (read from the other
+  // accumulator set), so the matrix pipe works in the shadow of the exponentials; the key operand
+  // of the tile's second sub-tile is read from LDS during the first one's MFMAs.
+  if constexpr (PASS == 1 && NSUB == 2 && MT <= 2) {
+    constexpr int NSLOT = KK * MT, EPS = (16 * MT + NSLOT - 1) / NSLOT;
+    f32x16 accA[MT], accB[MT];
+    bf16x8 kA[KK], kB[KK];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) accA[mt][i] = accB[mt][i] = -INFINITY;   // exp2 of "the sub-tile before the first" is 0
+    auto lds_read = [&](bf16x8& dst, int buf, int sub, int kk) __attribute__((always_inline)) {
+      Pack16 pk;
+      pk.u = *reinterpret_cast<const u32x4*>(&ktile[buf][(sub * 32 + l32) * ROWB + kk * 32 + half * 16]);
+      dst = pk.b;
+    };
+    // keys past the chunk end count as -inf (pkey0 = first key of the accumulators' sub-tile)
+    auto mask_tail = [&](f32x16 (&a)[MT], int pkey0) __attribute__((always_inline)) {
+      if (pkey0 + 32 > key_end) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (pkey0 + 8 * (i >> 2) + 4 * half + (i & 3) >= key_end) a[mt][i] = -INFINITY;
+      }
+    };
+    // one sub-tile: MFMAs into cur from operand kc, exponentials of prev; kn is filled for sub-tile nsub
+    auto step = [&](f32x16 (&cur)[MT], f32x16 (&prev)[MT], bf16x8 (&kc)[KK], bf16x8 (&kn)[KK], auto prefetch_c, int buf,
+                    int nsub) __attribute__((always_inline)) {
+      constexpr bool PREFETCH = decltype(prefetch_c)::value;
+#pragma unroll
+      for (int sl = 0; sl < NSLOT; ++sl) {
+        const int kk = sl / MT, mt = sl % MT;
+#pragma unroll
+        for (int j = 0; j < EPS; ++j) {
+          const int e = sl * EPS + j;
+          if (e < 16 * MT) s_run[e / 16] += fast_exp2(fmaf(prev[e / 16][e % 16], c_log2, -m_run[e / 16]));
+        }
+        if (kk == 0) {
+          f32x16 z;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) z[i] = 0.f;
+          cur[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[kk], qreg[mt][kk], z, 0, 0, 0);
+        } else {
+          cur[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[kk], qreg[mt][kk], cur[mt], 0, 0, 0);
+        }
+        if (PREFETCH && mt == MT - 1) lds_read(kn[kk], buf, nsub, kk);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto pipe_tile = [&](int t, u32x4 (&pf)[LPT], auto masked_c, auto first_c) __attribute__((always_inline)) {
+      constexpr bool MASKED = decltype(masked_c)::value;   // this tile or the one before may reach past key_end
+      constexpr bool FIRST = decltype(first_c)::value;
+      const int buf = t & 1;
+      const int key0 = key_begin + t * TK;
+      store_tile(pf, buf);
+      issue_tile(t + NPF, pf);
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) lds_read(kA[kk], buf, 0, kk);
+      if (MASKED) mask_tail(accB, key0 - 32);            // second sub-tile of the tile before
+      step(accA, accB, kA, kB, T{}, buf, 1);
+      if (FIRST || MASKED) mask_tail(accA, key0);
+      if (FIRST) {
+        // The reference of the exponentials is fixed by the lane's first 16 logits of the chunk (any
+        // finite reference gives the same log-sum-exp); later logits may exceed it by up to ~2^100
+        // before the sum overflows, which is detected below and repeated with a running maximum.
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          float mx = fmaxf(accA[mt][0], accA[mt][1]);
+#pragma unroll
+          for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(accA[mt][i], accA[mt][i + 1]));
+          const float mn = mx * c_log2;
+          m_run[mt] = mn == -INFINITY ? 0.f : mn;
+        }
+      }
+      step(accB, accA, kB, kA, F{}, buf, 0);
+    };
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) m_run[mt] = 0.f;
+    if (ntiles > NPF) {
+      pipe_tile(0, pf0, F{}, T{});
+      pipe_tile(1, pf1, F{}, F{});
+      for (int t0 = NPF; t0 < ntiles - NPF; t0 += NPF) {
+        pipe_tile(t0, pf0, F{}, F{});
+        pipe_tile(t0 + 1, pf1, F{}, F{});
+      }
+      pipe_tile(ntiles - 2, pf0, T{}, F{});
+      pipe_tile(ntiles - 1, pf1, T{}, F{});
+    } else {
+      pipe_tile(0, pf0, T{}, T{});
+      pipe_tile(1, pf1, T{}, F{});
+    }
+    // the exponentials of the last sub-tile
+    mask_tail(accB, key_begin + (ntiles - 1) * TK + 32);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(accB[mt][i], c_log2, -m_run[mt]));
+      s_run[mt] += sum;
+    }
+  } else if (PASS == 1) {
     // the first tile fixes the reference of the exponentials; only the last pair can reach past the chunk end
     if (ntiles > NPF) {
       do_tile(0, pf0, F{}, F{}, T{});

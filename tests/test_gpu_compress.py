@@ -209,6 +209,21 @@ def test_extreme_logits_take_the_running_maximum_path():
     assert rep["ranked"] == 4
 
 
+def test_extreme_logits_with_256_rows_per_head():
+    # the same situation on the shape of the long-context configurations (4 query heads x 64 window rows per KV head:
+    # the statistics pass that overlaps its exponentials with the next sub-tile's MFMAs), chunk tails included
+    w, Hq, Hkv, d = 64, 8, 2, 128
+    lay = wl.make_layer((114,), [2100 + 37, 700], Hq, Hkv, d, w, dtype="bf16")
+    three = wl.to_bf16_bits(np.full((d,), 3.0, dtype=np.float32))
+    small = wl.to_bf16_bits(np.random.default_rng(2).standard_normal((Hkv, 2837, d)).astype(np.float32) * 0.01)
+    lay.qwin[:] = three
+    lay.k[:] = small
+    lay.k[:, 900:980, :] = three
+    lay.k[:, 2137 + 300:2137 + 380, :] = three
+    rep = check(lay, np.array([w + 60, w + 9], dtype=np.int32))
+    assert rep["ranked"] == 4
+
+
 def test_batch_without_tokens():
     # every sequence empty: the inputs and outputs have no rows (torch hands out NULL pointers for
     # them); the call still has to succeed and write the offsets
