@@ -101,7 +101,8 @@ def main():
                 + len(ranked) * m * 4 * 2                          # importance written + read
                 + kept * 4                                         # kept indices
                 + kept * d * 2 * 2 * 2)                            # K and V rows read + written
-        return flops, byts, kept, len(ranked)
+        big_rows = int(sum(int(c) for c in np.diff(calls[l].offsets) if c > 256))   # rows the gather launch copies
+        return flops, byts, kept, len(ranked), big_rows
 
     for i in range(args.warmup):
         step(i)
@@ -177,9 +178,9 @@ def main():
                                           "p90": round(float(np.percentile(lat, 90)), 5), "n": int(nlat)},
                   "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
                   # the HBM-bound kernels against the chip peak: 4 B per ranked history key for the selection,
-                  # 1 KiB (K and V row, read + written) per kept row for the gather launch
+                  # 1 KiB (K and V row, read + written) per row of the segments the gather launch copies
                   "select_GBs": round(4.0 * (n - w) * float(np.mean([x[3] for x in work])) / (kernel_ms.get("select", float("nan")) * 1e-3) / 1e9, 1),
-                  "gather_GBs": round(float(np.mean([x[2] for x in work if x[2] > 0])) * d * 2 * 2 * 2 / (kernel_ms.get("gather", float("nan")) * 1e-3) / 1e9, 1),
+                  "gather_GBs": round(float(np.mean([x[4] for x in work if x[4] > 0] or [0.0])) * d * 2 * 2 * 2 / (kernel_ms.get("gather", float("nan")) * 1e-3) / 1e9, 1),
                   "kernel_launches_per_step": kernel_launches,
                   "kernel_sum_ms": round(sum(kernel_ms[k] * kernel_launches[k] for k in kernel_ms), 5)},
     }

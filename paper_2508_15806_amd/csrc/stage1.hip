@@ -376,7 +376,7 @@ __global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t hea
 // The keys are walked in super-chunks of kQkSuper keys, twice each (the second time they come
 // from cache): the first walk computes the logits with the 32x32x16 bf16 MFMA (a lane owns one
 // query row and 16 keys of a 32-key sub-tile) and updates, per lane, the running softmax
-// statistics, the needle mass and 16 running maxima; the maxima of the 4 lanes of a row are 64
+// statistics, the needle mass and 16 running maxima; the maxima of the 8 lanes of a row are 128
 // maxima of disjoint key subsets, and their K-th largest is a lower bound of the row's K-th
 // largest logit.  The second walk computes the logits again and appends those at or above the
 // bound (a few dozen per row) to the row's candidate list in LDS; lists are re-filtered with the
@@ -384,9 +384,11 @@ __global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t hea
 // (larger logit first, equal logits by lower position), turns the K winners into weights with
 // the row's log-sum-exp and splits them into WO / WD by needle membership.  A row whose list
 // overflows (many equal logits at the top) is flagged and redone by qk_fallback_kernel.
-constexpr int kQkThreads = 256;
+constexpr int kQkThreads = 512;      // 8 waves: 2 row blocks of 32 rows x 4 sub-tiles of 32 keys
+constexpr int kQkWaves = kQkThreads / 64;
 constexpr int kQkRows = 64;
-constexpr int kQkTile = 64;
+constexpr int kQkTile = 128;
+constexpr int kQkSubsets = 2 * (kQkTile / 32) * 16;   // key subsets per row whose maxima are tracked
 constexpr int kQkCand = 128;
 constexpr int kQkSuper = 2048;
 constexpr int kQkFallbackWGs = 128;
@@ -402,11 +404,10 @@ union QkPack16 {
 template <int DK>
 struct QkLds {
   static constexpr int ROWB = DK * 2 + 16;                 // padded key row: conflict-free 16-byte operand reads
-  unsigned char ktile[2][kQkTile * ROWB];
+  unsigned char ktile[2][kQkTile * ROWB];                   // between the walks: the subset maxima [row][(ks, half, i)]
   float cand_x[kQkRows][kQkCand];
   int32_t cand_p[kQkRows][kQkCand];
-  float mx[kQkRows][64];                                    // subset maxima of a row: (ks, half, i)
-  float st_m[kQkRows][4], st_s[kQkRows][4], st_t[kQkRows][4];
+  float st_m[kQkRows][8], st_s[kQkRows][8], st_t[kQkRows][8];
   float bound[kQkRows];
   uint32_t cnt[kQkRows];
   uint32_t ovf[kQkRows];
@@ -417,7 +418,7 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {
 }
 
 template <int DK>
-__global__ __launch_bounds__(kQkThreads, 1) void qk_cells_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ kmat,
+__global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ kmat,
                                                                  int Hq, int Hkv, int T, int n, int rowgroups,
                                                                  int needle_start, int needle_len, int topk, float c_log2,
                                                                  double* __restrict__ cells, unsigned char* __restrict__ overflow) {
@@ -430,6 +431,10 @@ __global__ __launch_bounds__(kQkThreads, 1) void qk_cells_kernel(const uint16_t*
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int rb = wv & 1, ks = wv >> 1, l32 = lane & 31, half = lane >> 5;
+  static_assert(sizeof(float) * kQkRows * kQkSubsets <= sizeof(S.ktile), "the subset maxima live in the tile buffers");
+  static_assert(kQkSubsets == 128 && kQkCand == 128 && kQkRows % kQkWaves == 0, "a lane holds two maxima / two candidates of a row");
+  float (*mxl)[kQkSubsets] = reinterpret_cast<float (*)[kQkSubsets]>(&S.ktile[0][0]);
+  constexpr int RPW = kQkRows / kQkWaves;            // rows a wave looks after between the walks
   const int G = Hq / Hkv, R = G * T;
   const int rg = blockIdx.x % rowgroups, seg = blockIdx.x / rowgroups;   // seg = l * Hkv + kvh
   const int l = seg / Hkv, kvh = seg % Hkv;
@@ -463,7 +468,7 @@ __global__ __launch_bounds__(kQkThreads, 1) void qk_cells_kernel(const uint16_t*
   const uint32_t piece_off = (uint32_t)(tid % CPR) * 16u;
   const int piece_row = tid / CPR;
   qk_u32x4 pf0[LPT], pf1[LPT];
-  // tiles of 64 keys of [key_lo, key_hi): HBM / cache -> registers -> LDS, two tiles in flight
+  // tiles of 128 keys of [key_lo, key_hi): HBM / cache -> registers -> LDS, two tiles in flight
   auto walk = [&](int key_lo, int key_hi, auto body) __attribute__((always_inline)) {
     const int ntile = (((key_hi - key_lo + kQkTile - 1) / kQkTile) + 1) & ~1;   // even; a surplus tile is fully masked
     auto issue = [&](int t, qk_u32x4 (&pf)[LPT]) __attribute__((always_inline)) {
@@ -534,17 +539,17 @@ __global__ __launch_bounds__(kQkThreads, 1) void qk_cells_kernel(const uint16_t*
       t_run = t_run * scale + tsum;
       m_run = mn;
     });
-    // bound of every row: the K-th largest of its 64 subset maxima; candidate lists filtered by it
+    // bound of every row: the K-th largest of its 128 subset maxima; candidate lists filtered by it
 #pragma unroll
-    for (int i = 0; i < 16; ++i) S.mx[r][(ks * 2 + half) * 16 + i] = mxs[i];
+    for (int i = 0; i < 16; ++i) mxl[r][(ks * 2 + half) * 16 + i] = mxs[i];
     __syncthreads();
-    for (int rr = wv * 16; rr < wv * 16 + 16; ++rr) {
-      const uint32_t mkey = float_key(S.mx[rr][lane]);
+    for (int rr = wv * RPW; rr < wv * RPW + RPW; ++rr) {
+      const uint32_t mkey0 = float_key(mxl[rr][lane]), mkey1 = float_key(mxl[rr][lane + 64]);
       uint32_t tkey = 0;
 #pragma unroll
       for (int b = 31; b >= 0; --b) {
         const uint32_t trial = tkey | (1u << b);
-        if ((uint32_t)__popcll(__ballot(mkey >= trial)) >= (uint32_t)topk) tkey = trial;
+        if ((uint32_t)(__popcll(__ballot(mkey0 >= trial)) + __popcll(__ballot(mkey1 >= trial))) >= (uint32_t)topk) tkey = trial;
       }
       const float nb = rr < nrows ? key_to_float(tkey) : INFINITY;
       const uint32_t c = S.cnt[rr];
@@ -593,18 +598,18 @@ __global__ __launch_bounds__(kQkThreads, 1) void qk_cells_kernel(const uint16_t*
     });
   }
 
-  // statistics of a row: its 4 lanes -> log-sum-exp and needle mass
+  // statistics of a row: its 8 lanes -> log-sum-exp and needle mass
   S.st_m[r][ks * 2 + half] = m_run;
   S.st_s[r][ks * 2 + half] = s_run;
   S.st_t[r][ks * 2 + half] = t_run;
   __syncthreads();
-  for (int rr = wv * 16; rr < min(wv * 16 + 16, nrows); ++rr) {
+  for (int rr = wv * RPW; rr < min(wv * RPW + RPW, nrows); ++rr) {
     float M = S.st_m[rr][0];
 #pragma unroll
-    for (int j = 1; j < 4; ++j) M = fmaxf(M, S.st_m[rr][j]);
+    for (int j = 1; j < 8; ++j) M = fmaxf(M, S.st_m[rr][j]);
     float ssum = 0.f, tsum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j) {
       const float f = __builtin_amdgcn_exp2f(S.st_m[rr][j] - M);
       ssum += S.st_s[rr][j] * f;
       tsum += S.st_t[rr][j] * f;
