@@ -685,8 +685,19 @@ __global__ __launch_bounds__(kS1Threads) void qk_fallback_kernel(const uint16_t*
     for (int i = 1; i < kS1Threads / 64; ++i) o += red[i];
     return o;
   };
-  for (int64_t row = blockIdx.x; row < nrows_total; row += gridDim.x) {
-    if (!overflow[row]) continue;                     // uniform over the workgroup
+  // rows blockIdx.x, blockIdx.x + gridDim.x, ... are this workgroup's; their flags are read 256 at a time
+  __shared__ int64_t todo[kS1Threads];
+  __shared__ uint32_t ntodo;
+  for (int64_t base = blockIdx.x; base < nrows_total; base += (int64_t)gridDim.x * kS1Threads) {
+    __syncthreads();
+    if (tid == 0) ntodo = 0;
+    __syncthreads();
+    const int64_t mine = base + (int64_t)tid * gridDim.x;
+    if (mine < nrows_total && overflow[mine]) todo[atomicAdd(&ntodo, 1u)] = mine;
+    __syncthreads();
+    const uint32_t cnt = ntodo;
+  for (uint32_t it = 0; it < cnt; ++it) {
+    const int64_t row = todo[it];
     const int64_t hq_l = row / T;                     // l * Hq + hq
     const int l = (int)(hq_l / Hq), hq = (int)(hq_l % Hq);
     const uint16_t* kb = kmat + ((int64_t)l * Hkv + hq / G) * n * DK;
@@ -719,6 +730,7 @@ __global__ __launch_bounds__(kS1Threads) void qk_fallback_kernel(const uint16_t*
     __syncthreads();
     row_cells_impl<false>(W, n, needle_start, needle_len, topk, cells + row * 4);
     __syncthreads();
+  }
   }
 }
 
