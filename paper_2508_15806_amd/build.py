@@ -12,6 +12,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslkv.so")
 
+ROCM_INCLUDE = os.path.join(os.environ.get("ROCM_PATH", "/opt/rocm"), "include")
+
 HIP_SOURCES = ["compress.hip", "stage1.hip"]
 HOST_SOURCES = ["slkv_host.cpp", "timing.cpp"]
 
@@ -36,8 +38,8 @@ def build(verbose=True):
         objs.append(obj)
     for src in HOST_SOURCES:
         obj = os.path.join(objdir, src + ".o")
-        # host arithmetic (budget allocation) must not be contracted into FMAs
-        run([hipcc] + COMMON + ["-ffp-contract=off", "-x", "hip", "--offload-arch=gfx950", "-c", os.path.join(CSRC, src), "-o", obj])
+        # plain C++ (no device pass); host arithmetic (budget allocation) must not be contracted into FMAs
+        run([hipcc] + COMMON + ["-ffp-contract=off", "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I", ROCM_INCLUDE, "-c", os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
     run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
     return LIB

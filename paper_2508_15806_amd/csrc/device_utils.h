@@ -1,4 +1,4 @@
-// Block-level building blocks (wave64): scans, reductions and a three-level radix select.
+// Block-level building blocks (wave64): scans, reductions and the digit search of the radix select.
 #ifndef SLKV_DEVICE_UTILS_H
 #define SLKV_DEVICE_UTILS_H
 
@@ -90,37 +90,6 @@ __device__ __forceinline__ void select_bin(const uint32_t* hist, uint32_t k, uin
     }
   }
   __syncthreads();
-}
-
-// K-th largest of `count` 32-bit keys by three histogram levels (11 + 11 + 10 bits).
-// key_at(j, key) returns false for elements that do not take part.  Returns the key of the
-// k-th largest element; *need_eq = how many elements equal to it belong to the top k.
-// hist: kHistBins words of LDS; sh_scan: NT/64 words; res: 2 words.
-template <int NT, class KeyFn>
-__device__ __forceinline__ uint32_t block_radix_select(KeyFn key_at, int64_t count, uint32_t k, uint32_t* hist,
-                                                        uint32_t* sh_scan, uint32_t* res, uint32_t* need_eq) {
-  uint32_t prefix = 0;
-#pragma unroll 1
-  for (int level = 0; level < 3; ++level) {
-    const int shift = level == 0 ? 21 : (level == 1 ? 10 : 0);
-    const int bits = level == 2 ? 10 : 11;
-    for (int i = threadIdx.x; i < kHistBins; i += NT) hist[i] = 0;
-    __syncthreads();
-    for (int64_t j = threadIdx.x; j < count; j += NT) {
-      uint32_t key;
-      if (key_at(j, key)) {
-        const bool in = level == 0 || (key >> (shift + bits)) == prefix;
-        if (in) atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1u);
-      }
-    }
-    __syncthreads();
-    select_bin<NT>(hist, k, sh_scan, res);
-    prefix = (prefix << bits) | res[0];
-    k = res[1];
-    __syncthreads();
-  }
-  *need_eq = k;
-  return prefix;
 }
 
 // Order-preserving map from fp32 bit patterns to unsigned integers (larger float -> larger key).
