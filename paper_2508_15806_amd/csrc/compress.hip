@@ -1185,11 +1185,20 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   uint32_t kmin = 0xffffffffu, kmax = 0u;
   pool_all();
   SLKV_STAMP(128 + seg, 1);
+  if (j0 + EPT <= m) {                             // every thread but the last ones with positions
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    key[e] = j0 + e < m ? score_key(p[e]) : kKeyNone;
-    kmin = min(kmin, key[e]);
-    if (key[e] != kKeyNone) kmax = max(kmax, key[e]);
+    for (int e = 0; e < EPT; ++e) {
+      key[e] = score_key(p[e]);
+      kmin = min(kmin, key[e]);
+      kmax = max(kmax, key[e]);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      key[e] = j0 + e < m ? score_key(p[e]) : kKeyNone;
+      kmin = min(kmin, key[e]);
+      if (key[e] != kKeyNone) kmax = max(kmax, key[e]);
+    }
   }
   if (write_pooled) {
 #pragma unroll
@@ -1255,9 +1264,13 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
         if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
       }
     } else {
+      // in [lo, hi] <=> key - lo <= hi - lo: a key below lo wraps to a difference above any span,
+      // and kKeyNone lies above every hi
 #pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (key[e] >= lo && key[e] <= hi) atomicAdd(&hist[(key[e] - lo) >> shift], 1u);
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t dk = key[e] - lo;
+        if (dk <= span1) atomicAdd(&hist[dk >> shift], 1u);
+      }
     }
     __syncthreads();
     if (level == 0) SLKV_STAMP(128 + seg, 3);
@@ -1273,9 +1286,10 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       // collect the scores of the chosen digit (their order does not matter for counting)
       if (tid == 0) res[0] = 0;
       __syncthreads();
+      const uint32_t span2 = hi - lo;
 #pragma unroll
       for (int e = 0; e < EPT; ++e)
-        if (key[e] >= lo && key[e] <= hi) {
+        if (key[e] - lo <= span2) {
           const uint32_t slot = atomicAdd(&res[0], 1u);
           if (slot < kCandCap) cand[slot] = key[e];
         }
@@ -1291,9 +1305,10 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   // ordered compaction: slot = (#greater before) + min(#equal before, need_eq)
   {
     uint32_t gmask = 0, emask = 0;                 // bit e: element e is above / equal to the threshold
+    const uint32_t above = kKeyNone - tau - 1u;     // tau < key < kKeyNone <=> key - tau - 1 < above
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      gmask |= (key[e] > tau && key[e] != kKeyNone) ? (1u << e) : 0u;
+      gmask |= (key[e] - tau - 1u < above) ? (1u << e) : 0u;
       emask |= key[e] == tau ? (1u << e) : 0u;
     }
     const uint32_t cg = __popc(gmask), ce = __popc(emask);
