@@ -24,8 +24,9 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel (the statistics pass) from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this same command (profiles/compress_layer_c3_avg256_rocprofv3.md, section 2):
-# 67600 KiB read + 130 KiB written.  A counter reading, not something this script can measure.
-MEASURED_TRAFFIC_BYTES = 69.4e6
+# 68134 KiB read (counter 34067.1 x 2.0, the factor a plain copy of known size gives) + 524 KiB
+# written.  A counter reading, not something this script can measure.
+MEASURED_TRAFFIC_BYTES = 70.3e6
 
 
 def parse():
