@@ -204,6 +204,7 @@ def main():
                 calls[l].run(dq[l], dk[l], dv[l])
         torch.cuda.current_stream().wait_stream(gs)
         torch.cuda.synchronize()
+        B.slkv_init()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=gs):
             for l in range(NL):

@@ -16,8 +16,10 @@
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every
- *     buffer; the library allocates no device memory and keeps no state between calls
- *     (the optional kernel-timing recorder at the end of this header aside).
+ *     buffer; the library allocates no device memory.  What it keeps between calls: per device,
+ *     that its one-time set-up has been done (slkv_init), the counters at the start of a
+ *     workspace (see slkv_compress_layer), and the optional kernel-timing recorder at the end
+ *     of this header.
  *   - slkv_score_heads, slkv_compress_layer and slkv_recompress_layer only enqueue work on `hip_stream` (a
  *     hipStream_t passed as void*, NULL = the default stream) and return without
  *     synchronising.  Host-side descriptors are consumed before the call returns.
@@ -57,6 +59,12 @@ const char* slkv_status_str(slkv_status s);
 const char* slkv_last_error(void);
 /* ABI version: major * 1000 + minor. */
 int32_t slkv_version(void);
+/* One-time set-up on the CURRENT device (host pointer arguments: none): raises the LDS limit of
+ * the selection kernels and looks up the scratch of slkv_compress_layer_static.  Optional: a
+ * call that finds its device not set up does this itself, which is why the first call on a
+ * device must not be the one a stream capture records unless slkv_init() has run there before.
+ * Thread-safe, idempotent, enqueues nothing on a stream.  SLKV_ERR_HIP if a HIP call fails. */
+slkv_status slkv_init(void);
 
 /* ------------------------------------------------------------------ Stage 1 -----------
  * Algorithm 1 (Section 3.2).  For every row W (length n) of every head: T_k = the `topk`

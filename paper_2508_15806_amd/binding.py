@@ -22,7 +22,7 @@ SLKV_AGG_MICRO, SLKV_AGG_MACRO = 0, 1
 STATUS_NAMES = {0: "SLKV_OK", 1: "SLKV_ERR_NULL", 2: "SLKV_ERR_BAD_ARG", 3: "SLKV_ERR_BAD_VALUE",
                 4: "SLKV_ERR_UNSUPPORTED", 5: "SLKV_ERR_WORKSPACE", 6: "SLKV_ERR_CAPACITY", 7: "SLKV_ERR_HIP"}
 
-EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_score_heads", "slkv_score_heads_ex", "slkv_score_heads_qk",
+EXPORTS = ["slkv_status_str", "slkv_last_error", "slkv_version", "slkv_init", "slkv_score_heads", "slkv_score_heads_ex", "slkv_score_heads_qk",
            "slkv_score_heads_qk_workspace_bytes",
            "slkv_score_heads_workspace_bytes", "slkv_allocate_budgets", "slkv_fixed_from_beta",
            "slkv_compacted_sizes", "slkv_workspace_bytes", "slkv_compress_layer", "slkv_compress_layer_static",
@@ -144,6 +144,11 @@ def _stream(stream):
 
 def slkv_version():
     return int(lib().slkv_version())
+
+
+def slkv_init():
+    """One-time set-up on the current device (optional; see the header)."""
+    _check(lib().slkv_init())
 
 
 def slkv_fixed_from_beta(avg_budget, beta):

@@ -1584,28 +1584,43 @@ static void launch_select(int nseg, int blocks, hipStream_t st, const TAB& tab, 
               (const uint32_t*)blockhist, kept_idx, d_out_offsets, ga);
 }
 
-// select_resident_kernel needs more LDS than a kernel gets by default: the limit is raised once per
-// kernel instance and device (not a stream operation; the first call on a device should still
-// not be the one a graph capture records).
-template <int RADIUS, class TAB>
-static hipError_t launch_select_resident_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
-                                           const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets,
-                                           const GatherArgs& ga) {
+// select_resident_kernel needs more LDS than a kernel gets by default: the limit is raised for all
+// of its instances once per device, by slkv_init() or by the first call that selects on that
+// device (setting it is not a stream operation, but the first call on a device should still not
+// be the one a graph capture records).
+template <int RADIUS>
+static hipError_t raise_lds_limit() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, SegTable>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsBytes);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, SegTableDev>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsBytes);
+}
+
+static hipError_t ensure_device_init() {
   static std::mutex mu;
   static uint64_t done = 0;                      // bit per device
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  {
-    std::lock_guard<std::mutex> lk(mu);
-    const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t(1) << dev) : 0;
-    if (!(done & bit)) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, TAB>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsBytes);
-      if (e != hipSuccess) return e;
-      done |= bit;
-    }
-  }
+  std::lock_guard<std::mutex> lk(mu);
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t(1) << dev) : 0;
+  if (done & bit) return hipSuccess;
+  if ((e = raise_lds_limit<0>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<1>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<2>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<3>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<-1>()) != hipSuccess) return e;
+  done |= bit;
+  return hipSuccess;
+}
+
+template <int RADIUS, class TAB>
+static hipError_t launch_select_resident_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
+                                           const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets,
+                                           const GatherArgs& ga) {
+  const hipError_t e = ensure_device_init();
+  if (e != hipSuccess) return e;
   const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
   SLKV_LAUNCH((select_resident_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), kResLdsBytes, st, tab, g.w,
                      pool_kernel, g.pool, (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
@@ -1841,6 +1856,14 @@ static slkv_status static_scratch(void** out) {
   }
   *out = ptrs[dev];
   return SLKV_OK;
+}
+
+extern "C" slkv_status slkv_init(void) {
+  clear_error();
+  const hipError_t e = ensure_device_init();
+  if (e != hipSuccess) return fail(SLKV_ERR_HIP, "device set-up failed: %s", hipGetErrorString(e));
+  void* ptr = nullptr;
+  return static_scratch(&ptr);
 }
 
 extern "C" slkv_status slkv_workspace_bytes(const slkv_layer_desc* desc, size_t* bytes) {

@@ -115,7 +115,7 @@ const char* slkv_status_str(slkv_status s) {
 
 const char* slkv_last_error(void) { return g_err; }
 
-int32_t slkv_version(void) { return 1002; }
+int32_t slkv_version(void) { return 1003; }
 
 int32_t slkv_fixed_from_beta(int32_t avg_budget, double beta) {
   if (avg_budget < 0 || !(beta >= 1.0)) return -1;

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2508_15806_amd import api
+from paper_2508_15806_amd import binding as B
 from paper_2508_15806_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -33,7 +34,8 @@ def test_captured_call_replays_like_eager():
         torch.cuda.synchronize()
         refs.append(outputs(call))
     assert not np.array_equal(refs[0][2], refs[1][2])
-    # capture one call on a side stream
+    # capture one call on a side stream (the device's one-time set-up is not a stream operation)
+    B.slkv_init()
     g = torch.cuda.CUDAGraph()
     s = torch.cuda.Stream()
     s.wait_stream(torch.cuda.current_stream())
