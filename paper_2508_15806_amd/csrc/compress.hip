@@ -1450,6 +1450,26 @@ static void make_plan(const Geometry& g, Plan& p) {
     ch = (ch + 31) / 32 * 32;
     ch = std::max<int64_t>(32, std::min<int64_t>(ch, 1 << 16));
   }
+  // All chunks should be resident at once (two 256-thread workgroups per CU on 256 CUs): the
+  // partial last chunk of every segment can push the count a little over that, and the surplus
+  // workgroups would then run alone in a second round that doubles the kernel's time.  Lengthen
+  // the chunk, by up to a quarter, until the count fits.
+  {
+    constexpr int64_t kSlots = 512;
+    const int64_t granule = g.dtype == SLKV_BF16 ? 128 : 32;
+    auto count = [&](int64_t c) {
+      int64_t total = 0;
+      for (const Seg& s : g.segs)
+        if (seg_ranked(s.n, g.w, s.cap)) total += (s.n - g.w + c - 1) / c;
+      return total;
+    };
+    if (count(ch) > kSlots)
+      for (int64_t c = ch + granule; c <= ch + ch / 4 && c <= (1 << 16); c += granule)
+        if (count(c) <= kSlots) {
+          ch = c;
+          break;
+        }
+  }
   p.CH = (int)ch;
   int64_t chunks = 0;
   p.hist_blocks = 0;
