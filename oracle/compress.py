@@ -31,13 +31,13 @@ POOL_AVG = 2
 
 
 def bf16_bits_to_f64(a):
-    """Exact widening of bfloat16 bit patterns (uint16) or fp32 values to float64."""
+    """Exact widening of bfloat16 bit patterns (uint16), fp16 or fp32 values to float64."""
     a = np.asarray(a)
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
-    if a.dtype == np.float32 or a.dtype == np.float64:
+    if a.dtype == np.float16 or a.dtype == np.float32 or a.dtype == np.float64:
         return a.astype(np.float64)
-    raise TypeError("expected float32 or uint16 (bf16 bits), got %s" % a.dtype)
+    raise TypeError("expected float32, float16 or uint16 (bf16 bits), got %s" % a.dtype)
 
 
 def window_importance(q_group, k_hist):

@@ -7,11 +7,16 @@ import torch
 from . import binding as B
 
 
+DTYPES = {"f32": (B.SLKV_F32, torch.float32), "bf16": (B.SLKV_BF16, torch.bfloat16), "f16": (B.SLKV_F16, torch.float16)}
+
+
 def to_device(arr, dtype, device="cuda"):
-    """numpy fp32 array, or uint16 array of bfloat16 bit patterns -> device tensor."""
+    """numpy fp32 / fp16 array, or uint16 array of bfloat16 bit patterns -> device tensor."""
     if dtype == "bf16":
         t = torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).to(device)
         return t.view(torch.bfloat16)
+    if dtype == "f16":
+        return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float16)).to(device)
     return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
 
 
@@ -31,10 +36,10 @@ class LayerCall:
         contiguous [Hkv][T][d]."""
         T = int(cu_seqlens[-1])
         self.dtype = dtype
-        self.layer = B.Layer(B.SLKV_BF16 if dtype == "bf16" else B.SLKV_F32, B_, Hq, Hkv, d, w, cu_seqlens,
+        self.layer = B.Layer(DTYPES[dtype][0], B_, Hq, Hkv, d, w, cu_seqlens,
                              budgets, k_strides or (d, T * d), v_strides or (d, T * d), pool_kernel, pool)
         self.offsets, self.total_kept = B.slkv_compacted_sizes(self.layer)
-        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        tdt = DTYPES[dtype][1]
         rows = max(self.total_kept, 1)
         self.k_out = torch.empty((rows, d), dtype=tdt, device=device)
         self.v_out = torch.empty((rows, d), dtype=tdt, device=device)
@@ -57,10 +62,10 @@ class RaggedCall:
     def __init__(self, dtype, B_, Hq, Hkv, d, w, in_offsets, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX,
                  device="cuda", debug_scores=False, positions=True):
         rows_in = int(in_offsets[-1])
-        self.rag = B.Ragged(B.SLKV_BF16 if dtype == "bf16" else B.SLKV_F32, B_, Hq, Hkv, d, w, in_offsets, budgets,
+        self.rag = B.Ragged(DTYPES[dtype][0], B_, Hq, Hkv, d, w, in_offsets, budgets,
                             pool_kernel, pool)
         self.offsets, self.total_kept = B.slkv_recompress_sizes(self.rag)
-        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        tdt = DTYPES[dtype][1]
         rows = max(self.total_kept, 1)
         self.k_out = torch.empty((rows, d), dtype=tdt, device=device)
         self.v_out = torch.empty((rows, d), dtype=tdt, device=device)

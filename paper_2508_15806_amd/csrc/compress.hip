@@ -74,6 +74,17 @@ union Pack16 {
   bf16x8 b;
 };
 
+// 32x32x16 MFMA on eight 16-bit elements per lane and operand: bfloat16, or IEEE half when F16
+// (the registers are typed bf16x8 either way; only the instruction reads them differently).
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma16(bf16x8 a, bf16x8 b, f32x16 c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 // Segment of a block / row: the largest s with prefix[s] <= x (prefix non-decreasing, prefix[nseg] > x).
 __device__ __forceinline__ int find_segment(const int32_t* prefix, int nseg, int x) {
   int lo = 0, hi = nseg - 1;
@@ -170,7 +181,7 @@ __device__ __forceinline__ void finish_stats_chunk(const TAB& tab, int seg, int 
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA scoring.  One workgroup (4 waves) owns one chunk of history keys of one segment.
+// MFMA scoring of 16-bit inputs (bfloat16, or half when F16).  One workgroup (4 waves) owns one chunk of history keys of one segment.
 // K is staged in LDS in tiles of 64 keys (two buffers); up to kPrefetch further tiles are in
 // flight from HBM into registers.  Wave (rb, ks) holds rows [rb*32*MT, (rb+1)*32*MT) of the
 // G*w query rows in registers for the whole chunk and works on the 32-key sub-tiles
@@ -183,7 +194,7 @@ __device__ __forceinline__ void finish_stats_chunk(const TAB& tab, int seg, int 
 constexpr int kTileKeys = 64;
 constexpr int kPrefetch = 2;
 
-template <int DK, int MT, int RB, int PASS, class TAB>
+template <int DK, int MT, int RB, int PASS, bool F16, class TAB>
 __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(const TAB tab, const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ kmat, int64_t k_stride_tok,
                                                          int64_t k_stride_head, int R, int Rpad, int w, int CH,
@@ -312,9 +323,9 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           if (PASS == 1)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk], qreg[mt][kk], acc, 0, 0, 0);
+            acc = mfma16<F16>(kreg[kk], qreg[mt][kk], acc);
           else
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[mt][kk], kreg[kk], acc, 0, 0, 0);
+            acc = mfma16<F16>(qreg[mt][kk], kreg[kk], acc);
         }
         if (PASS == 1) {
           // lane: query row mt*32 + l32, keys key0 + 8*(i/4) + 4*half + i%4
@@ -428,9 +439,9 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
           f32x16 z;
 #pragma unroll
           for (int i = 0; i < 16; ++i) z[i] = 0.f;
-          cur[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[kk], qreg[mt][kk], z, 0, 0, 0);
+          cur[mt] = mfma16<F16>(kc[kk], qreg[mt][kk], z);
         } else {
-          cur[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[kk], qreg[mt][kk], cur[mt], 0, 0, 0);
+          cur[mt] = mfma16<F16>(kc[kk], qreg[mt][kk], cur[mt]);
         }
         if (PREFETCH && mt == MT - 1) lds_read(kn[kk], buf, nsub, kk);
         __builtin_amdgcn_sched_barrier(0);
@@ -1443,7 +1454,7 @@ static void make_plan(const Geometry& g, Plan& p) {
   for (const Seg& s : g.segs)
     if (seg_ranked(s.n, g.w, s.cap)) keys += s.n - g.w;
   int64_t ch = (keys + 511) / 512;
-  if (g.dtype == SLKV_BF16) {                 // MFMA kernels: pairs of 64-key tiles
+  if (g.dtype != SLKV_F32) {                  // MFMA kernels: pairs of 64-key tiles
     ch = (ch + 127) / 128 * 128;
     ch = std::max<int64_t>(256, std::min<int64_t>(ch, 1 << 16));
   } else {                                    // fp32 kernels: 32-key tiles
@@ -1456,7 +1467,7 @@ static void make_plan(const Geometry& g, Plan& p) {
   // the chunk, by up to a quarter, until the count fits.
   {
     constexpr int64_t kSlots = 512;
-    const int64_t granule = g.dtype == SLKV_BF16 ? 128 : 32;
+    const int64_t granule = g.dtype != SLKV_F32 ? 128 : 32;
     auto count = [&](int64_t c) {
       int64_t total = 0;
       for (const Seg& s : g.segs)
@@ -1540,28 +1551,28 @@ static void ragged_geometry(const slkv_ragged_desc* d, Geometry& g) {
   }
 }
 
-template <int DK, int MT, int RB, class TAB>
+template <int DK, int MT, int RB, bool F16, class TAB>
 static void launch_bf16(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                         uint32_t* tickets) {
   if (pass == 1)
-    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, F16, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
                        (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
                        lse, tickets);
   else
-    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, F16, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
                        (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
                        lse, tickets);
 }
 
-template <int DK, class TAB>
+template <int DK, bool F16, class TAB>
 static void launch_bf16_rows(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                              const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                              uint32_t* tickets) {
-  if (p.R <= 64) launch_bf16<DK, 1, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-  else if (p.R <= 128) launch_bf16<DK, 2, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-  else if (p.R <= 256) launch_bf16<DK, 2, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-  else launch_bf16<DK, 4, 4>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  if (p.R <= 64) launch_bf16<DK, 1, 2, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else if (p.R <= 128) launch_bf16<DK, 2, 2, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else if (p.R <= 256) launch_bf16<DK, 2, 4, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else launch_bf16<DK, 4, 4, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
 }
 
 template <class TAB>
@@ -1569,8 +1580,11 @@ static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, con
                          const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                          uint32_t* tickets) {
   if (g.dtype == SLKV_BF16) {
-    if (g.d == 128) launch_bf16_rows<128>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-    else launch_bf16_rows<64>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    if (g.d == 128) launch_bf16_rows<128, false>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    else launch_bf16_rows<64, false>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  } else if (g.dtype == SLKV_F16) {
+    if (g.d == 128) launch_bf16_rows<128, true>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    else launch_bf16_rows<64, true>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
   SLKV_LAUNCH((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
@@ -1693,7 +1707,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
                         d_importance, d_pooled, d_workspace};
   for (const void* ptr : ptrs)
     if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(SLKV_ERR_BAD_ARG, "device pointer %p not 16-byte aligned", ptr);
-  const int elt = g.dtype == SLKV_BF16 ? 2 : 4;
+  const int elt = g.dtype == SLKV_F32 ? 4 : 2;
   const int64_t S = (int64_t)g.segs.size();
   if (S / g.Hkv * g.Hq * g.w >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "B*Hq*w >= 2^31");
   int64_t total_kept = 0;

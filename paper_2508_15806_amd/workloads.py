@@ -45,7 +45,7 @@ class LayerInputs:
     """One layer's inputs for the compression pass.
 
     qwin [B, Hq, w, d]; k, v [Hkv, T, d] (sequences packed along T);
-    cu_seqlens [B+1] int64.  dtype "f32" (float32 arrays) or "bf16" (uint16 bit
+    cu_seqlens [B+1] int64.  dtype "f32" (float32 arrays), "f16" (float16 arrays) or "bf16" (uint16 bit
     patterns)."""
     dtype: str
     B: int
@@ -91,8 +91,10 @@ def make_layer(seed_key, seqlens, Hq, Hkv, d, w, dtype="bf16", bias_frac=0.0, bi
                 k[h, cu[b] + pos, :] += np.float32(bias_sigma) * qv
     if dtype == "bf16":
         q, k, v = to_bf16_bits(q), to_bf16_bits(k), to_bf16_bits(v)
+    elif dtype == "f16":
+        q, k, v = q.astype(np.float16), k.astype(np.float16), v.astype(np.float16)
     elif dtype != "f32":
-        raise ValueError("dtype must be 'f32' or 'bf16'")
+        raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
     return LayerInputs(dtype, B, Hq, Hkv, d, w, cu, q, k, v)
 
 
@@ -141,8 +143,10 @@ def make_ragged_cache(seed_key, seg_lens, B, Hq, Hkv, d, w, dtype="bf16", bias_f
             k[r0 + at, :] += np.float32(bias_sigma) * qv
     if dtype == "bf16":
         q, k, v = to_bf16_bits(q), to_bf16_bits(k), to_bf16_bits(v)
+    elif dtype == "f16":
+        q, k, v = q.astype(np.float16), k.astype(np.float16), v.astype(np.float16)
     elif dtype != "f32":
-        raise ValueError("dtype must be 'f32' or 'bf16'")
+        raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
     return RaggedCache(dtype, B, Hq, Hkv, d, w, offs, q, k, v, pos)
 
 

@@ -6,7 +6,7 @@ import oracle
 from paper_2508_15806_amd import api
 from paper_2508_15806_amd import binding as B
 
-TOL = {"bf16": 2e-3, "f32": 1e-5}      # relative tolerance on importance scores (task statement)
+TOL = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-5}      # relative tolerance on importance scores (task statement; fp16 as bf16)
 
 BAND = 4096                            # guard bytes on either side of every output / workspace buffer
 SENTINEL = 0xA5
@@ -52,7 +52,7 @@ def run_gpu(lay, budgets, pool_kernel=7, pool=B.SLKV_POOL_MAX, token_major=False
         ks = (lay.Hkv * lay.d, lay.d)
         vs = (lay.Hkv * (lay.d + pad), lay.d + pad)
         k_host = np.ascontiguousarray(np.transpose(lay.k, (1, 0, 2)))
-        v_host = np.full((lay.v.shape[1], lay.Hkv, lay.d + pad), 0x7F7F if lay.dtype == "bf16" else 1e30, dtype=lay.v.dtype)
+        v_host = np.full((lay.v.shape[1], lay.Hkv, lay.d + pad), {"bf16": 0x7F7F, "f16": 6e4, "f32": 1e30}[lay.dtype], dtype=lay.v.dtype)
         v_host[:, :, :lay.d] = np.transpose(lay.v, (1, 0, 2))
     call = api.LayerCall(lay.dtype, lay.B, lay.Hq, lay.Hkv, lay.d, lay.w, lay.cu_seqlens, budgets,
                          pool_kernel, pool, debug_scores=True, k_strides=ks, v_strides=vs)

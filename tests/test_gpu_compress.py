@@ -63,6 +63,25 @@ def test_bf16_row_shapes_and_ragged_tails(Hq, Hkv, w, d):
     check(lay, bud)
 
 
+@pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 16, 128), (8, 2, 32, 128), (4, 4, 24, 64), (32, 8, 16, 64),
+                                        (16, 4, 64, 128), (16, 2, 64, 64)])
+def test_fp16_row_shapes_and_ragged_tails(Hq, Hkv, w, d):
+    # IEEE half inputs through the same MFMA kernels (32 to 512 rows per KV head, both head dims)
+    lay = wl.make_layer((131, Hq, w, d), [1000 + w + 7, 333 + w], Hq, Hkv, d, w, dtype="f16", bias_frac=0.03)
+    assert lay.k.dtype == np.float16
+    bud = np.array([w + 40 + 13 * h for h in range(Hkv)], dtype=np.int32)
+    check(lay, bud)
+
+
+def test_fp16_long_history_and_token_major():
+    lay = wl.make_layer((132,), [40000 + 64 + 9, 700], 8, 2, 128, 64, dtype="f16", bias_frac=0.02)
+    rep = check(lay, np.array([900, 150], dtype=np.int32))                  # the 700-token sequence fits the first head's capacity
+    assert rep["ranked"] == 3 and rep["tolerant"] == 0
+    lay = wl.make_layer((133,), [1500 + 11, 0, 260], 8, 4, 128, 16, dtype="f16", bias_frac=0.04)
+    rep = check(lay, np.array([300, 16, 90, 2000], dtype=np.int32), token_major=True)
+    assert rep["ranked"] == 3 and rep["tolerant"] == 0
+
+
 @pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 8, 64), (4, 2, 32, 128), (8, 1, 40, 64)])
 def test_fp32_shapes(Hq, Hkv, w, d):
     lay = wl.make_layer((102, Hq, w, d), [700 + w + 5, 90], Hq, Hkv, d, w, dtype="f32", bias_frac=0.03)

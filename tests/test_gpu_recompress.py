@@ -32,13 +32,14 @@ def test_heads_of_different_lengths_bf16():
     assert rep["ranked"] >= 6
 
 
-@pytest.mark.parametrize("Hq,Hkv,w,d,dtype", [(4, 2, 8, 64, "f32"), (8, 2, 32, 128, "bf16"), (8, 8, 24, 64, "bf16")])
+@pytest.mark.parametrize("Hq,Hkv,w,d,dtype", [(4, 2, 8, 64, "f32"), (8, 2, 32, 128, "bf16"), (8, 8, 24, 64, "bf16"),
+                                              (8, 2, 32, 128, "f16")])
 def test_shapes(Hq, Hkv, w, d, dtype):
     rng = np.random.default_rng(7)
     lens = rng.integers(w + 1, 900, size=3 * Hkv).tolist()
     rc = wl.make_ragged_cache((202, Hq, w), lens, 3, Hq, Hkv, d, w, dtype=dtype, bias_frac=0.04)
     bud = np.array([w + 20 + 37 * h for h in range(Hkv)], dtype=np.int32)
-    check(rc, bud, positions=(dtype == "bf16"))
+    check(rc, bud, positions=(dtype != "f32"))
 
 
 def test_offsets_need_not_start_at_zero():

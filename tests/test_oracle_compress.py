@@ -106,6 +106,20 @@ def test_bf16_widening_is_exact():
     assert np.array_equal(wl.to_bf16_bits(wl.bf16_bits_to_f32(b)), b)
 
 
+def test_fp16_widening_is_exact_and_the_layer_equals_its_fp32_copy():
+    h = np.array([1.0, -1.0, 3.140625, 0.0, 6.103515625e-05, 65504.0], dtype=np.float16)
+    assert oracle.bf16_bits_to_f64(h).tolist() == [1.0, -1.0, 3.140625, 0.0, 2.0 ** -14, 65504.0]
+    # a half-precision layer and the same values stored as fp32 are the same problem
+    lay = wl.make_layer((41,), [300, 77], 4, 2, 64, 16, dtype="f16", bias_frac=0.05)
+    bud = np.array([60, 100], dtype=np.int32)
+    a = oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, bud, lay.w, 7)
+    b = oracle.compress_layer(lay.qwin.astype(np.float32), lay.k.astype(np.float32), lay.v.astype(np.float32),
+                              lay.cu_seqlens, bud, lay.w, 7)
+    for sa, sb in zip(a["segments"], b["segments"]):
+        assert np.array_equal(sa["kept_idx"], sb["kept_idx"]) and np.array_equal(sa["importance"], sb["importance"])
+    assert a["k_out"].dtype == np.float16 and np.array_equal(a["k_out"].astype(np.float32), b["k_out"])
+
+
 @pytest.mark.parametrize("kernel", [1, 3, 7, 9])
 def test_max_pool_matches_scipy_and_loop(kernel):
     x = np.random.default_rng(6).random(101)
