@@ -22,11 +22,25 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the dominant kernel (the statistics pass) from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs of this same command (profiles/compress_layer_c3_avg256_rocprofv3.md, section 2):
-# 68134 KiB read (counter 34067.1 x 2.0, the factor a plain copy of known size gives) + 524 KiB
-# written.  A counter reading, not something this script can measure.
-MEASURED_TRAFFIC_BYTES = 70.3e6
+# HBM bytes per launch of the dominant kernel (the statistics pass): a counter reading (rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this same command), not something this script can measure.  It is read
+# from the table of the committed summary, so that it cannot go stale against it.
+PROFILE_SUMMARY = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                               "compress_layer_c3_avg256_rocprofv3.md")
+
+
+def measured_traffic_bytes(path=PROFILE_SUMMARY):
+    """FETCH (scaled, KiB) + WRITE (KiB) of the pass-1 row of the summary's traffic table, in bytes; None if absent."""
+    try:
+        with open(path) as f:
+            for line in f:
+                cells = [c.strip() for c in line.split("|")]
+                # | kernel | FETCH_SIZE | x 2.0 -> KiB read | WRITE_SIZE -> KiB written |
+                if len(cells) >= 6 and cells[1].startswith("score_bf16_kernel<128,2,4,1") and "MiB" in cells[3]:
+                    return (float(cells[3].split()[0]) + float(cells[4])) * 1024.0
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def parse():
@@ -151,15 +165,16 @@ def main():
     flops_launch = float(np.mean(ranked_flops)) if ranked_flops else 0.0
     dom_ms = kernel_ms.get(dom, float("nan"))
     achieved_tflops = flops_launch / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    traffic = measured_traffic_bytes()
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved_tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES, "avg_ms": round(dom_ms, 5),
+                "traffic": traffic, "avg_ms": round(dom_ms, 5),
                 "timing": "start/stop events carried by each launch of the kernel (hipExtLaunchKernelGGL), mean over the timed steps",
                 "flops_per_launch": flops_launch,
                 # the same launch against the HBM roof (K of the ranked heads read once per pass)
-                "hbm_GBs": round(MEASURED_TRAFFIC_BYTES / (dom_ms * 1e-3) / 1e9, 1) if dom_ms > 0 else 0.0,
-                "hbm_frac": round(MEASURED_TRAFFIC_BYTES / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if dom_ms > 0 else 0.0}
+                "hbm_GBs": round(traffic / (dom_ms * 1e-3) / 1e9, 1) if traffic and dom_ms > 0 else None,
+                "hbm_frac": round(traffic / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic and dom_ms > 0 else None}
 
     out = {
         "metric": "prefix KV tokens compressed/sec per layer (1 GPU)",

@@ -724,6 +724,7 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelBlock = 4096;           // history positions per phase-A block
 constexpr int kSelEPT = 32;
+constexpr int kSelEPTMid = 8, kSelEPTSmall = 2;   // shorter histories: fewer positions per thread in the one-workgroup kernel
 constexpr int kSelRound = kSelThreads * kSelEPT;
 constexpr int kSelHaloMax = kMaxPool / 2;
 constexpr int kSelRankMax = 256;          // lists up to this length are ranked by direct counting
@@ -1074,14 +1075,18 @@ constexpr int kResStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * 
 constexpr int kResCandidates = 3072;   // scores of one first-level digit that the LDS list can hold
 constexpr size_t kResLdsBytes = (size_t)(kResStageFloats + kResCandidates) * sizeof(float);
 
-__device__ __forceinline__ int pad_idx(int i) { return i + (i >> 5); }
+// index into the staging array: one word of padding per thread's positions, so that the threads
+// of a wave read their consecutive positions from different banks
+template <int EPT>
+__device__ __forceinline__ int pad_idx(int i) { return i + i / EPT; }
 
-template <int RADIUS, class TAB>   // pooling radius known at compile time (0..3), or -1: any radius, window read from LDS
+template <int RADIUS, int EPT_, class TAB>   // pooling radius known at compile time (0..3), or -1: any radius, window read from LDS;
+                                             // EPT_: positions per thread (the history is at most 1024 * EPT_ positions)
 __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB tab, int w, int pool_kernel, int pool_mode,
                                                                       int write_pooled, const float* __restrict__ imp,
                                                                       float* __restrict__ pooled, int32_t* __restrict__ kept_idx,
                                                                       int64_t* __restrict__ d_out_offsets, const GatherArgs ga) {
-  constexpr int NT = kSelThreads, EPT = kSelEPT, ROUND = kSelRound;   // the history is at most ROUND positions
+  constexpr int NT = kSelThreads, EPT = EPT_, ROUND = NT * EPT_;   // the history is at most ROUND positions
   extern __shared__ float stage[];
   __shared__ uint32_t hist[kHistBins];
   __shared__ int32_t sh_pos[kInlineGatherRows];
@@ -1142,18 +1147,18 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
 #pragma unroll
     for (int c = 0; c < EPT; ++c) {
       const int s = c * NT + tid, j = base - radius + s;
-      stage[pad_idx(s)] = (j >= 0 && j < m) ? ld[c] : fill;
+      stage[pad_idx<EPT>(s)] = (j >= 0 && j < m) ? ld[c] : fill;
     }
     if (tid < 2 * radius) {
       const int s = ROUND + tid, j = base - radius + s;
-      stage[pad_idx(s)] = (j >= 0 && j < m) ? ld[EPT] : fill;
+      stage[pad_idx<EPT>(s)] = (j >= 0 && j < m) ? ld[EPT] : fill;
     }
     __syncthreads();
     if (RADIUS >= 0) {
       constexpr int RR = RADIUS >= 0 ? RADIUS : 0;
       float v[EPT + 2 * RR + 2];
 #pragma unroll
-      for (int e = 0; e < EPT + 2 * RR; ++e) v[e] = stage[pad_idx(EPT * tid + e)];
+      for (int e = 0; e < EPT + 2 * RR; ++e) v[e] = stage[pad_idx<EPT>(EPT * tid + e)];
       v[EPT + 2 * RR] = v[EPT + 2 * RR + 1] = fill;
       if (is_max) {
         // window maxima by doubling: widths 2 and 4, then two overlapping pieces cover 2*RR+1
@@ -1177,9 +1182,9 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     } else {
 #pragma unroll 1
       for (int e = 0; e < EPT; ++e) {
-        float a = stage[pad_idx(EPT * tid + e)];
+        float a = stage[pad_idx<EPT>(EPT * tid + e)];
         for (int t = 1; t <= 2 * radius; ++t) {
-          const float x = stage[pad_idx(EPT * tid + e + t)];
+          const float x = stage[pad_idx<EPT>(EPT * tid + e + t)];
           a = is_max ? fmaxf(a, x) : a + x;
         }
         p[e] = is_max ? a : a * inv_p;
@@ -1622,13 +1627,23 @@ static void launch_select(int nseg, int blocks, hipStream_t st, const TAB& tab, 
 // of its instances once per device, by slkv_init() or by the first call that selects on that
 // device (setting it is not a stream operation, but the first call on a device should still not
 // be the one a graph capture records).
-template <int RADIUS>
+template <int RADIUS, int EPT>
 static hipError_t raise_lds_limit() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, SegTable>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, EPT, SegTable>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsBytes);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, SegTableDev>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&select_resident_kernel<RADIUS, EPT, SegTableDev>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResLdsBytes);
+}
+
+template <int EPT>
+static hipError_t raise_lds_limits() {
+  hipError_t e;
+  if ((e = raise_lds_limit<0, EPT>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<1, EPT>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<2, EPT>()) != hipSuccess) return e;
+  if ((e = raise_lds_limit<3, EPT>()) != hipSuccess) return e;
+  return raise_lds_limit<-1, EPT>();
 }
 
 static hipError_t ensure_device_init() {
@@ -1640,25 +1655,39 @@ static hipError_t ensure_device_init() {
   std::lock_guard<std::mutex> lk(mu);
   const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t(1) << dev) : 0;
   if (done & bit) return hipSuccess;
-  if ((e = raise_lds_limit<0>()) != hipSuccess) return e;
-  if ((e = raise_lds_limit<1>()) != hipSuccess) return e;
-  if ((e = raise_lds_limit<2>()) != hipSuccess) return e;
-  if ((e = raise_lds_limit<3>()) != hipSuccess) return e;
-  if ((e = raise_lds_limit<-1>()) != hipSuccess) return e;
+  if ((e = raise_lds_limits<kSelEPT>()) != hipSuccess) return e;
+  if ((e = raise_lds_limits<kSelEPTMid>()) != hipSuccess) return e;
+  if ((e = raise_lds_limits<kSelEPTSmall>()) != hipSuccess) return e;
   done |= bit;
   return hipSuccess;
 }
 
-template <int RADIUS, class TAB>
-static hipError_t launch_select_resident_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
+template <int RADIUS, int EPT, class TAB>
+static hipError_t launch_select_resident_e(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
                                            const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets,
                                            const GatherArgs& ga) {
   const hipError_t e = ensure_device_init();
   if (e != hipSuccess) return e;
   const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
-  SLKV_LAUNCH((select_resident_kernel<RADIUS, TAB>), dim3(ns), dim3(kSelThreads), kResLdsBytes, st, tab, g.w,
+  SLKV_LAUNCH((select_resident_kernel<RADIUS, EPT, TAB>), dim3(ns), dim3(kSelThreads), kResLdsBytes, st, tab, g.w,
                      pool_kernel, g.pool, (int)write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
   return hipSuccess;
+}
+
+// Positions per thread: the fewest of 2, 8, 32 whose round holds the longest ranked history (every
+// wave runs through all of a thread's positions, whether or not the history reaches them).
+template <int RADIUS, class TAB>
+static hipError_t launch_select_resident_r(int ns, hipStream_t st, const TAB& tab, const Geometry& g, bool write_pooled,
+                                           const float* imp, float* pooled, int32_t* kept_idx, int64_t* d_out_offsets,
+                                           const GatherArgs& ga) {
+  int64_t longest = 0;
+  for (const Seg& sg : g.segs)
+    if (seg_ranked(sg.n, g.w, sg.cap)) longest = std::max<int64_t>(longest, sg.n - g.w);
+  if (longest <= kSelThreads * kSelEPTSmall)
+    return launch_select_resident_e<RADIUS, kSelEPTSmall>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
+  if (longest <= kSelThreads * kSelEPTMid)
+    return launch_select_resident_e<RADIUS, kSelEPTMid>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
+  return launch_select_resident_e<RADIUS, kSelEPT>(ns, st, tab, g, write_pooled, imp, pooled, kept_idx, d_out_offsets, ga);
 }
 
 template <class TAB>
