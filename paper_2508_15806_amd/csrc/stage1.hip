@@ -373,17 +373,17 @@ __global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t hea
 // Algorithm 1): the attention rows are never written anywhere.  One workgroup owns 64 query rows
 // of one KV head (the T decode steps of its G query heads) and all n keys.
 //
-// The keys are walked in super-chunks of kQkSuper keys, twice each (the second time they come
-// from cache): the first walk computes the logits with the 32x32x16 bf16 MFMA (a lane owns one
-// query row and 16 keys of a 32-key sub-tile) and updates, per lane, the running softmax
-// statistics, the needle mass and 16 running maxima; the maxima of the 8 lanes of a row are 128
-// maxima of disjoint key subsets, and their K-th largest is a lower bound of the row's K-th
-// largest logit.  The second walk computes the logits again and appends those at or above the
-// bound (a few dozen per row) to the row's candidate list in LDS; lists are re-filtered with the
-// tighter bound after every super-chunk.  At the end a wave per row ranks its candidates exactly
-// (larger logit first, equal logits by lower position), turns the K winners into weights with
-// the row's log-sum-exp and splits them into WO / WD by needle membership.  A row whose list
-// overflows (many equal logits at the top) is flagged and redone by qk_fallback_kernel.
+// The keys are walked in super-chunks of kQkSuper keys with the 32x32x16 bf16 MFMA (a lane owns
+// one query row and 16 keys of a 32-key sub-tile), keeping per lane the running softmax statistics
+// and the needle mass.  Logits at or above the row's bound are appended to the row's candidate
+// list in LDS; after every super-chunk the bound becomes the K-th largest entry of the list (the
+// exact K-th largest logit so far) and the list is cut back to the entries at or above it.  Only
+// the first super-chunk, which has no bound to start from, is walked twice: its first walk finds
+// a bound from subset maxima (below), its second collects.  So the keys are read 1 + 2048/n
+// times.  At the end a wave per row ranks its candidates exactly (larger logit first, equal logits
+// by lower position), turns the K winners into weights with the row's log-sum-exp and splits
+// them into WO / WD by needle membership.  A row whose list overflows (many equal logits at the
+// top, or logits that keep rising along the context) is flagged and redone by qk_fallback_kernel.
 constexpr int kQkThreads = 512;      // 8 waves: 2 row blocks of 32 rows x 4 sub-tiles of 32 keys
 constexpr int kQkWaves = kQkThreads / 64;
 constexpr int kQkRows = 64;
@@ -513,89 +513,129 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
     __syncthreads();                                  // the tile buffers are free again
   };
 
-  for (int sc0 = 0; sc0 < n; sc0 += kQkSuper) {
-    const int sc1 = min(n, sc0 + kQkSuper);
-    // first walk: softmax statistics, needle mass, subset maxima
-    walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
-      float mx = x[0];
+  // softmax statistics and needle mass of one MFMA tile's 16 logits of this lane's row
+  auto stats = [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
+    float mx = x[0];
 #pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-      const float mn = fmaxf(m_run, mx);
-      const float mu = mn == -INFINITY ? 0.f : mn;
-      const float scale = __builtin_amdgcn_exp2f(m_run - mu);
-      float sum = 0.f, tsum = 0.f;
-      const bool near_needle = key0 + 32 > needle_start && key0 < ne;     // wave-uniform up to `half`
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+    const float mn = fmaxf(m_run, mx);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    const float scale = __builtin_amdgcn_exp2f(m_run - mu);
+    float sum = 0.f, tsum = 0.f;
+    const bool near_needle = key0 + 32 > needle_start && key0 < ne;     // wave-uniform up to `half`
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float e = __builtin_amdgcn_exp2f(x[i] - mu);
-        sum += e;
-        if (near_needle) {
-          const int key = key0 + 8 * (i >> 2) + (i & 3);
-          tsum += (key >= needle_start && key < ne) ? e : 0.f;
-        }
-        mxs[i] = fmaxf(mxs[i], x[i]);
+    for (int i = 0; i < 16; ++i) {
+      const float e = __builtin_amdgcn_exp2f(x[i] - mu);
+      sum += e;
+      if (near_needle) {
+        const int key = key0 + 8 * (i >> 2) + (i & 3);
+        tsum += (key >= needle_start && key < ne) ? e : 0.f;
       }
-      s_run = s_run * scale + sum;
-      t_run = t_run * scale + tsum;
-      m_run = mn;
-    });
-    // bound of every row: the K-th largest of its 128 subset maxima; candidate lists filtered by it
+    }
+    s_run = s_run * scale + sum;
+    t_run = t_run * scale + tsum;
+    m_run = mn;
+  };
+  // the logits at or above the bound join the row's list
+  auto collect = [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) mxl[r][(ks * 2 + half) * 16 + i] = mxs[i];
-    __syncthreads();
-    for (int rr = wv * RPW; rr < wv * RPW + RPW; ++rr) {
-      const uint32_t mkey0 = float_key(mxl[rr][lane]), mkey1 = float_key(mxl[rr][lane + 64]);
-      uint32_t tkey = 0;
-#pragma unroll
-      for (int b = 31; b >= 0; --b) {
-        const uint32_t trial = tkey | (1u << b);
-        if ((uint32_t)(__popcll(__ballot(mkey0 >= trial)) + __popcll(__ballot(mkey1 >= trial))) >= (uint32_t)topk) tkey = trial;
-      }
-      const float nb = rr < nrows ? key_to_float(tkey) : INFINITY;
-      const uint32_t c = S.cnt[rr];
-      if (c > (uint32_t)kQkCand) {                    // the list overflowed: the row goes to the fallback
-        if (lane == 0) {
-          S.ovf[rr] = 1;
-          S.cnt[rr] = 0;
-          S.bound[rr] = INFINITY;
-        }
-      } else {
-        const float x0 = lane < (int)c ? S.cand_x[rr][lane] : -INFINITY, x1 = lane + 64 < (int)c ? S.cand_x[rr][lane + 64] : -INFINITY;
-        const int32_t p0 = S.cand_p[rr][lane], p1 = S.cand_p[rr][lane + 64];
-        const bool k0 = lane < (int)c && x0 >= nb, k1 = lane + 64 < (int)c && x1 >= nb;
-        const unsigned long long m0 = __ballot(k0), m1 = __ballot(k1);
-        const uint32_t n0 = (uint32_t)__popcll(m0);
-        const uint32_t lb0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m0, 0u));
-        const uint32_t lb1 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, 0u));
-        if (k0) {
-          S.cand_x[rr][lb0] = x0;
-          S.cand_p[rr][lb0] = p0;
-        }
-        if (k1) {
-          S.cand_x[rr][n0 + lb1] = x1;
-          S.cand_p[rr][n0 + lb1] = p1;
-        }
-        if (lane == 0) {
-          S.cnt[rr] = n0 + (uint32_t)__popcll(m1);
-          if (!S.ovf[rr]) S.bound[rr] = nb;
+    for (int i = 0; i < 16; ++i) {
+      if (x[i] >= bound) {
+        const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
+        if (slot < (uint32_t)kQkCand) {
+          S.cand_x[r][slot] = x[i];
+          S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
         }
       }
     }
+  };
+  // K-th largest of two values per lane (valid where v0 / v1) by bisection on the key bits; the
+  // whole wave calls it.  With fewer than K valid values the result is the key 0.
+  auto kth_key = [&](uint32_t k0, bool v0, uint32_t k1, bool v1) __attribute__((always_inline)) {
+    uint32_t tkey = 0;
+#pragma unroll
+    for (int b = 31; b >= 0; --b) {
+      const uint32_t trial = tkey | (1u << b);
+      if ((uint32_t)(__popcll(__ballot(v0 && k0 >= trial)) + __popcll(__ballot(v1 && k1 >= trial))) >= (uint32_t)topk) tkey = trial;
+    }
+    return tkey;
+  };
+  // A wave sets the new bound nb of row rr and drops the list entries below it (an overflowed
+  // list sends the row to the fallback).
+  auto refilter = [&](int rr, float nb) __attribute__((always_inline)) {
+    const uint32_t c = S.cnt[rr];
+    if (c > (uint32_t)kQkCand) {
+      if (lane == 0) {
+        S.ovf[rr] = 1;
+        S.cnt[rr] = 0;
+        S.bound[rr] = INFINITY;
+      }
+    } else {
+      const float x0 = lane < (int)c ? S.cand_x[rr][lane] : -INFINITY, x1 = lane + 64 < (int)c ? S.cand_x[rr][lane + 64] : -INFINITY;
+      const int32_t p0 = S.cand_p[rr][lane], p1 = S.cand_p[rr][lane + 64];
+      const bool k0 = lane < (int)c && x0 >= nb, k1 = lane + 64 < (int)c && x1 >= nb;
+      const unsigned long long m0 = __ballot(k0), m1 = __ballot(k1);
+      const uint32_t n0 = (uint32_t)__popcll(m0);
+      const uint32_t lb0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m0, 0u));
+      const uint32_t lb1 = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m1, 0u));
+      if (k0) {
+        S.cand_x[rr][lb0] = x0;
+        S.cand_p[rr][lb0] = p0;
+      }
+      if (k1) {
+        S.cand_x[rr][n0 + lb1] = x1;
+        S.cand_p[rr][n0 + lb1] = p1;
+      }
+      if (lane == 0) {
+        S.cnt[rr] = n0 + (uint32_t)__popcll(m1);
+        if (!S.ovf[rr]) S.bound[rr] = nb;
+      }
+    }
+  };
+
+  for (int sc0 = 0; sc0 < n; sc0 += kQkSuper) {
+    const int sc1 = min(n, sc0 + kQkSuper);
+    if (sc0 == 0) {
+      // The first super-chunk is walked twice (the second time its keys come from cache): no
+      // bound exists yet, so the first walk also tracks 16 running maxima per lane; the maxima of
+      // the 8 lanes of a row are 128 maxima of disjoint key subsets, and their K-th largest is a
+      // lower bound of the row's K-th largest logit.  The second walk collects the candidates.
+      walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
+        stats(key0, x);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mxs[i] = fmaxf(mxs[i], x[i]);
+      });
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mxl[r][(ks * 2 + half) * 16 + i] = mxs[i];
+      __syncthreads();
+      for (int rr = wv * RPW; rr < wv * RPW + RPW; ++rr) {
+        const uint32_t tkey = kth_key(float_key(mxl[rr][lane]), true, float_key(mxl[rr][lane + 64]), true);
+        if (lane == 0) S.bound[rr] = rr < nrows ? key_to_float(tkey) : INFINITY;
+      }
+      __syncthreads();
+      bound = row_ok ? S.bound[r] : INFINITY;
+      walk(sc0, sc1, collect);
+    } else {
+      // Later super-chunks are walked once: the bound is the exact K-th largest logit of the keys
+      // seen so far, so about K * (keys in the super-chunk) / (keys before it) new candidates
+      // join the K carried ones.
+      walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
+        stats(key0, x);
+        collect(key0, x);
+      });
+    }
+    // every list now holds all logits so far that are at or above the row's bound, hence the K
+    // largest: their K-th largest is the new bound, and the entries below it are dropped
+    for (int rr = wv * RPW; rr < wv * RPW + RPW; ++rr) {
+      const uint32_t c = min(S.cnt[rr], (uint32_t)kQkCand);
+      const bool v0 = lane < (int)c, v1 = lane + 64 < (int)c;
+      const uint32_t tkey = kth_key(float_key(S.cand_x[rr][lane]), v0, float_key(S.cand_x[rr][lane + 64]), v1);
+      // (a list shorter than K cannot happen for a row of finite logits; -inf keeps everything)
+      const float nb = rr < nrows ? (c >= (uint32_t)topk ? key_to_float(tkey) : -INFINITY) : INFINITY;
+      refilter(rr, nb);
+    }
     __syncthreads();
     bound = row_ok ? S.bound[r] : INFINITY;
-    // second walk: the logits at or above the bound join the row's list
-    walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (x[i] >= bound) {
-          const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
-          if (slot < (uint32_t)kQkCand) {
-            S.cand_x[r][slot] = x[i];
-            S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
-          }
-        }
-      }
-    });
   }
 
   // statistics of a row: its 8 lanes -> log-sum-exp and needle mass
