@@ -373,24 +373,34 @@ __global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t hea
 // Algorithm 1): the attention rows are never written anywhere.  One workgroup owns 64 query rows
 // of one KV head (the T decode steps of its G query heads) and all n keys.
 //
-// The keys are walked in super-chunks of kQkSuper keys with the 32x32x16 bf16 MFMA (a lane owns
-// one query row and 16 keys of a 32-key sub-tile), keeping per lane the running softmax statistics
-// and the needle mass.  Logits at or above the row's bound are appended to the row's candidate
-// list in LDS; after every super-chunk the bound becomes the K-th largest entry of the list (the
-// exact K-th largest logit so far) and the list is cut back to the entries at or above it.  Only
-// the first super-chunk, which has no bound to start from, is walked twice: its first walk finds
-// a bound from subset maxima (below), its second collects.  So the keys are read 1 + 2048/n
-// times.  At the end a wave per row ranks its candidates exactly (larger logit first, equal logits
-// by lower position), turns the K winners into weights with the row's log-sum-exp and splits
-// them into WO / WD by needle membership.  A row whose list overflows (many equal logits at the
-// top, or logits that keep rising along the context) is flagged and redone by qk_fallback_kernel.
-constexpr int kQkThreads = 512;      // 8 waves: 2 row blocks of 32 rows x 4 sub-tiles of 32 keys
+// With 64 rows per key the work is bound by reading the keys (64 flop per byte), so the kernel is
+// built as a stream: each of the 8 waves takes every 8th sub-tile of 32 keys, loads it straight
+// from memory into the operand registers of the 32x32x16 bf16 MFMA (a lane: 16 bytes of one key
+// row per load; nothing is staged in LDS and the waves never wait for each other inside a chunk),
+// keeps two sub-tiles in flight, and multiplies it with both 32-row tiles of the queries, which
+// stay in registers.  A lane owns two query rows (one per row tile) and, per sub-tile, 16 keys of
+// each: it keeps the running softmax statistics and the needle mass of its rows.
+// Logits at or above the row's bound are appended to the row's candidate list in LDS.  The keys
+// are cut into chunks: the first kQkFirst keys, then chunks half as long as everything before
+// them.  After every chunk the waves meet, the bound of a row becomes the K-th largest entry of
+// its list (the K-th largest logit so far, resolved to its leading bits) and the list is cut back
+// to the entries at or above it; since a chunk holds at most half as many keys as came before, about K/2 new entries
+// join the K carried ones.  Only the first chunk, which has no bound to start from, is walked
+// twice: its first walk tracks 16 running maxima per lane and row, the 16 lanes of a row give 256
+// maxima of disjoint key subsets, and their K-th largest is a lower bound of the row's K-th
+// largest logit; its second walk collects.  So the keys are read 1 + kQkFirst/n times.
+// At the end a wave per row ranks its candidates exactly (larger logit first, equal logits by
+// lower position), turns the K winners into weights with the row's log-sum-exp and splits them
+// into WO / WD by needle membership.  A row whose list overflows (many equal logits at the top,
+// or logits that keep rising along the context) is flagged and redone by qk_fallback_kernel.
+constexpr int kQkThreads = 512;      // 8 waves
 constexpr int kQkWaves = kQkThreads / 64;
-constexpr int kQkRows = 64;
-constexpr int kQkTile = 128;
-constexpr int kQkSubsets = 2 * (kQkTile / 32) * 16;   // key subsets per row whose maxima are tracked
+constexpr int kQkRows = 64;          // two row tiles of 32
+constexpr int kQkStripe = 32 * kQkWaves;   // keys the waves take together: chunk ends are multiples of it
+constexpr int kQkFirst = 4 * kQkStripe;    // keys of the first chunk
+constexpr int kQkSubsets = kQkWaves * 2 * 16;   // key subsets per row whose maxima are tracked in the first walk
 constexpr int kQkCand = 128;
-constexpr int kQkSuper = 2048;
+constexpr int kQkBoundBits = 18;     // leading key bits that the bound of a row is resolved to between chunks
 constexpr int kQkFallbackWGs = 128;
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 qk_bf16x8;
@@ -403,11 +413,9 @@ union QkPack16 {
 
 template <int DK>
 struct QkLds {
-  static constexpr int ROWB = DK * 2 + 16;                 // padded key row: conflict-free 16-byte operand reads
-  unsigned char ktile[2][kQkTile * ROWB];                   // between the walks: the subset maxima [row][(ks, half, i)]
-  float cand_x[kQkRows][kQkCand];
+  float cand_x[kQkRows][kQkCand];                           // first walk: the subset maxima [row][(wave, half, i)]
   int32_t cand_p[kQkRows][kQkCand];
-  float st_m[kQkRows][8], st_s[kQkRows][8], st_t[kQkRows][8];
+  float st_m[kQkRows][2 * kQkWaves], st_s[kQkRows][2 * kQkWaves], st_t[kQkRows][2 * kQkWaves];
   float bound[kQkRows];
   uint32_t cnt[kQkRows];
   uint32_t ovf[kQkRows];
@@ -416,6 +424,12 @@ struct QkLds {
 __device__ __forceinline__ float key_to_float(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
 }
+// a key whose low bits were cleared, as a bound: a value at or below the one the key came from
+// (a truncated key of -inf reads as a NaN pattern: -inf then)
+__device__ __forceinline__ float bound_from_key(uint32_t key) {
+  const float f = key_to_float(key);
+  return f != f ? -INFINITY : f;
+}
 
 template <int DK>
 __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ kmat,
@@ -423,18 +437,17 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
                                                                  int needle_start, int needle_len, int topk, float c_log2,
                                                                  double* __restrict__ cells, unsigned char* __restrict__ overflow) {
   constexpr int KK = DK / 16;
-  constexpr int ROWB = QkLds<DK>::ROWB;
-  constexpr int CPR = DK * 2 / 16;                  // 16-byte pieces per key row
-  constexpr int LPT = kQkTile * CPR / kQkThreads;   // pieces per thread per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char qk_smem[];
   QkLds<DK>& S = *reinterpret_cast<QkLds<DK>*>(qk_smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int rb = wv & 1, ks = wv >> 1, l32 = lane & 31, half = lane >> 5;
-  static_assert(sizeof(float) * kQkRows * kQkSubsets <= sizeof(S.ktile), "the subset maxima live in the tile buffers");
-  static_assert(kQkSubsets == 128 && kQkCand == 128 && kQkRows % kQkWaves == 0, "a lane holds two maxima / two candidates of a row");
-  float (*mxl)[kQkSubsets] = reinterpret_cast<float (*)[kQkSubsets]>(&S.ktile[0][0]);
-  constexpr int RPW = kQkRows / kQkWaves;            // rows a wave looks after between the walks
+  const int l32 = lane & 31, half = lane >> 5;
+  static_assert(sizeof(float) * kQkSubsets <= sizeof(S.cand_x[0]) + sizeof(S.cand_p[0]) &&
+                    offsetof(QkLds<DK>, cand_p) == sizeof(S.cand_x),
+                "the subset maxima of the first walk live in the (still empty) candidate lists");
+  static_assert(kQkSubsets == 256 && kQkCand == 128 && kQkRows % kQkWaves == 0, "a lane holds four maxima / two candidates of a row");
+  float (*mxl)[kQkSubsets] = reinterpret_cast<float (*)[kQkSubsets]>(&S.cand_x[0][0]);
+  constexpr int RPW = kQkRows / kQkWaves;            // rows a wave looks after between the chunks
   const int G = Hq / Hkv, R = G * T;
   const int rg = blockIdx.x % rowgroups, seg = blockIdx.x / rowgroups;   // seg = l * Hkv + kvh
   const int l = seg / Hkv, kvh = seg % Hkv;
@@ -443,8 +456,6 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
   const int64_t rowid0 = ((int64_t)l * Hq + (int64_t)kvh * G) * T + row0;   // first global row of this workgroup
   const uint16_t* qbase = q + rowid0 * DK;
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(kmat + (int64_t)seg * n * DK);
-  const int r = rb * 32 + l32;                       // this lane's row inside the workgroup
-  const bool row_ok = r < nrows;
   const int ne = needle_start + needle_len;
 
   for (int i = tid; i < kQkRows; i += kQkThreads) {
@@ -452,75 +463,79 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
     S.ovf[i] = 0;
     S.bound[i] = INFINITY;
   }
-  qk_bf16x8 qreg[KK];
+  // this lane's rows inside the workgroup: l32 and 32 + l32
+  qk_bf16x8 qreg[2][KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    QkPack16 p;
-    p.u = *reinterpret_cast<const qk_u32x4*>(qbase + (int64_t)min(r, nrows - 1) * DK + kk * 16 + half * 8);
-    qreg[kk] = p.b;
-  }
-  float m_run = -INFINITY, s_run = 0.f, t_run = 0.f;   // running maximum, sum of exp2(x - max), the same over the needle
-  float mxs[16];
+  for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-  for (int i = 0; i < 16; ++i) mxs[i] = -INFINITY;
-  float bound = INFINITY;
-
-  const uint32_t piece_off = (uint32_t)(tid % CPR) * 16u;
-  const int piece_row = tid / CPR;
-  qk_u32x4 pf0[LPT], pf1[LPT];
-  // tiles of 128 keys of [key_lo, key_hi): HBM / cache -> registers -> LDS, two tiles in flight
-  auto walk = [&](int key_lo, int key_hi, auto body) __attribute__((always_inline)) {
-    const int ntile = (((key_hi - key_lo + kQkTile - 1) / kQkTile) + 1) & ~1;   // even; a surplus tile is fully masked
-    auto issue = [&](int t, qk_u32x4 (&pf)[LPT]) __attribute__((always_inline)) {
-      const int key0 = key_lo + t * kQkTile + piece_row;
-#pragma unroll
-      for (int i = 0; i < LPT; ++i) {
-        const int key = min(key0 + i * (kQkThreads / CPR), key_hi - 1);
-        pf[i] = *reinterpret_cast<const qk_u32x4*>(kbase + ((uint32_t)key * (uint32_t)(DK * 2) + piece_off));
-      }
-    };
-    auto tile = [&](int t, qk_u32x4 (&pf)[LPT]) __attribute__((always_inline)) {
-      const int buf = t & 1;
-#pragma unroll
-      for (int i = 0; i < LPT; ++i) {
-        const int idx = i * kQkThreads + tid;
-        *reinterpret_cast<qk_u32x4*>(&S.ktile[buf][(idx / CPR) * ROWB + (idx % CPR) * 16]) = pf[i];
-      }
-      issue(t + 2, pf);
-      __syncthreads();
-      qk_f32x16 acc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        QkPack16 p;
-        p.u = *reinterpret_cast<const qk_u32x4*>(&S.ktile[buf][(ks * 32 + l32) * ROWB + kk * 32 + half * 16]);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[kk], acc, 0, 0, 0);
-      }
-      // lane: row r, keys key0 + 8*(i/4) + 4*half + i%4
-      const int key0 = key_lo + t * kQkTile + ks * 32 + 4 * half;
-      float x[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) x[i] = key0 + 8 * (i >> 2) + (i & 3) < key_hi ? acc[i] * c_log2 : -INFINITY;
-      body(key0, x);
-    };
-    issue(0, pf0);
-    issue(1, pf1);
-    for (int t = 0; t < ntile; t += 2) {
-      tile(t, pf0);
-      tile(t + 1, pf1);
+    for (int kk = 0; kk < KK; ++kk) {
+      QkPack16 p;
+      p.u = *reinterpret_cast<const qk_u32x4*>(qbase + (int64_t)min(mt * 32 + l32, nrows - 1) * DK + kk * 16 + half * 8);
+      qreg[mt][kk] = p.b;
     }
-    __syncthreads();                                  // the tile buffers are free again
-  };
+  float m_run[2] = {-INFINITY, -INFINITY}, s_run[2] = {0.f, 0.f}, t_run[2] = {0.f, 0.f};   // running maximum, sum of exp2(x - max), the same over the needle
+  float bound[2] = {INFINITY, INFINITY};
+  __syncthreads();
 
-  // softmax statistics and needle mass of one MFMA tile's 16 logits of this lane's row
-  auto stats = [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
-    float mx = x[0];
+  // one sub-tile of 32 keys starting at key_s: 16 bytes of key row (key_s + l32) per load (clamped at the end of the keys)
+  auto issue = [&](int key_s, qk_u32x4 (&kf)[KK]) __attribute__((always_inline)) {
+    const uint32_t off = (uint32_t)min(key_s + l32, n - 1) * (uint32_t)(DK * 2) + (uint32_t)half * 16u;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const qk_u32x4*>(kbase + (off + (uint32_t)kk * 32u));
+  };
+  // logits of the sub-tile against both row tiles; body(mt, key0, x): lane's row mt*32 + l32, keys key0 + 8*(i/4) + i%4
+  auto sub_tile = [&](int key_s, const qk_u32x4 (&kf)[KK], auto body) __attribute__((always_inline)) {
+    qk_f32x16 acc[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      QkPack16 p;
+      p.u = kf[kk];
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[0][kk], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[1][kk], acc[1], 0, 0, 0);
+    }
+    const int key0 = key_s + 4 * half;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      float x[16];
+      if (key_s + 32 > n) {                           // the last sub-tile of the keys: mask what lies beyond
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = key0 + 8 * (i >> 2) + (i & 3) < n ? acc[mt][i] * c_log2 : -INFINITY;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = acc[mt][i] * c_log2;
+      }
+      body(mt, key0, x);
+    }
+  };
+  // this wave's sub-tiles of [key_lo, key_hi) (multiples of kQkStripe, key_hi clipped to n), two in flight
+  // (preloaded: the wave's first sub-tile is already on its way into kfA, requested by prefetch())
+  qk_u32x4 kfA[KK], kfB[KK];
+  auto prefetch = [&](int key_lo, int key_hi) __attribute__((always_inline)) {
+    if (key_lo + wv * 32 < key_hi) issue(key_lo + wv * 32, kfA);
+  };
+  auto walk = [&](int key_lo, int key_hi, bool preloaded, auto body) __attribute__((always_inline)) {
+    int ks = key_lo + wv * 32;
+    if (!preloaded && ks < key_hi) issue(ks, kfA);
+    for (; ks < key_hi; ks += 2 * kQkStripe) {
+      const int kb = ks + kQkStripe;
+      if (kb < key_hi) issue(kb, kfB);
+      sub_tile(ks, kfA, body);
+      if (kb + kQkStripe < key_hi) issue(kb + kQkStripe, kfA);
+      if (kb < key_hi) sub_tile(kb, kfB, body);
+    }
+  };
+  // softmax statistics and needle mass of 16 logits of row tile mt
+  auto stats = [&](int mt, int key0, const float (&x)[16], float& mx) __attribute__((always_inline)) {
+    mx = x[0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-    const float mn = fmaxf(m_run, mx);
+    const float mn = fmaxf(m_run[mt], mx);
     const float mu = mn == -INFINITY ? 0.f : mn;
-    const float scale = __builtin_amdgcn_exp2f(m_run - mu);
+    const float scale = __builtin_amdgcn_exp2f(m_run[mt] - mu);
     float sum = 0.f, tsum = 0.f;
     const bool near_needle = key0 + 32 > needle_start && key0 < ne;     // wave-uniform up to `half`
 #pragma unroll
@@ -532,31 +547,45 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
         tsum += (key >= needle_start && key < ne) ? e : 0.f;
       }
     }
-    s_run = s_run * scale + sum;
-    t_run = t_run * scale + tsum;
-    m_run = mn;
+    s_run[mt] = s_run[mt] * scale + sum;
+    t_run[mt] = t_run[mt] * scale + tsum;
+    m_run[mt] = mn;
   };
-  // the logits at or above the bound join the row's list
-  auto collect = [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
+  // the logits at or above the bound join the row's list (mx: the largest of the 16)
+  auto collect = [&](int mt, int key0, const float (&x)[16], float mx) __attribute__((always_inline)) {
+    if (mx >= bound[mt]) {
+      const int r = mt * 32 + l32;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if (x[i] >= bound) {
-        const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
-        if (slot < (uint32_t)kQkCand) {
-          S.cand_x[r][slot] = x[i];
-          S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
+      for (int i = 0; i < 16; ++i) {
+        if (x[i] >= bound[mt]) {
+          const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
+          if (slot < (uint32_t)kQkCand) {
+            S.cand_x[r][slot] = x[i];
+            S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
+          }
         }
       }
     }
   };
-  // K-th largest of two values per lane (valid where v0 / v1) by bisection on the key bits; the
-  // whole wave calls it.  With fewer than K valid values the result is the key 0.
-  auto kth_key = [&](uint32_t k0, bool v0, uint32_t k1, bool v1) __attribute__((always_inline)) {
+  // Bounds of the wave's RPW = 8 rows at once: 8 lanes per row, NE keys per lane (0 = no entry).
+  // Bisection on the leading kQkBoundBits bits of the keys: the result (the same in the 8 lanes
+  // of a row) is the largest value with the remaining bits clear that at least K keys reach, so
+  // it lies at or below the K-th largest key and within 2^-(kQkBoundBits - 9) of it (relative, in
+  // the logit).  All on the vector unit: no lane-mask round trips through scalar registers.
+  auto group_kth = [&](auto& keys, auto ne_c) __attribute__((always_inline)) {
+    constexpr int NE = decltype(ne_c)::value;
     uint32_t tkey = 0;
-#pragma unroll
-    for (int b = 31; b >= 0; --b) {
+#pragma unroll 1
+    for (int b = 31; b >= 32 - kQkBoundBits; --b) {
       const uint32_t trial = tkey | (1u << b);
-      if ((uint32_t)(__popcll(__ballot(v0 && k0 >= trial)) + __popcll(__ballot(v1 && k1 >= trial))) >= (uint32_t)topk) tkey = trial;
+      uint32_t c = 0;
+#pragma unroll
+      for (int j = 0; j < NE; ++j) c += keys[j] >= trial ? 1u : 0u;
+      // sum over the 8 lanes of the row: neighbours in the quad, then the other quad (DPP, no LDS crossbar)
+      c += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+      c += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+      c += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)c, 0x141, 0xF, 0xF, false);   // row_half_mirror
+      if (c >= (uint32_t)topk) tkey = trial;
     }
     return tkey;
   };
@@ -593,63 +622,94 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
     }
   };
 
-  for (int sc0 = 0; sc0 < n; sc0 += kQkSuper) {
-    const int sc1 = min(n, sc0 + kQkSuper);
-    if (sc0 == 0) {
-      // The first super-chunk is walked twice (the second time its keys come from cache): no
-      // bound exists yet, so the first walk also tracks 16 running maxima per lane; the maxima of
-      // the 8 lanes of a row are 128 maxima of disjoint key subsets, and their K-th largest is a
-      // lower bound of the row's K-th largest logit.  The second walk collects the candidates.
-      walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
-        stats(key0, x);
+  int c_lo = 0, c_hi = min(n, kQkFirst);
+  {
+    // The first chunk, first walk: statistics and 16 running maxima per lane and row
+    float mxs[2][16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mxs[i] = fmaxf(mxs[i], x[i]);
-      });
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mxl[r][(ks * 2 + half) * 16 + i] = mxs[i];
-      __syncthreads();
-      for (int rr = wv * RPW; rr < wv * RPW + RPW; ++rr) {
-        const uint32_t tkey = kth_key(float_key(mxl[rr][lane]), true, float_key(mxl[rr][lane + 64]), true);
-        if (lane == 0) S.bound[rr] = rr < nrows ? key_to_float(tkey) : INFINITY;
-      }
-      __syncthreads();
-      bound = row_ok ? S.bound[r] : INFINITY;
-      walk(sc0, sc1, collect);
-    } else {
-      // Later super-chunks are walked once: the bound is the exact K-th largest logit of the keys
-      // seen so far, so about K * (keys in the super-chunk) / (keys before it) new candidates
-      // join the K carried ones.
-      walk(sc0, sc1, [&](int key0, const float (&x)[16]) __attribute__((always_inline)) {
-        stats(key0, x);
-        collect(key0, x);
-      });
+      for (int i = 0; i < 16; ++i) mxs[mt][i] = -INFINITY;
+    walk(c_lo, c_hi, false, [&](int mt, int key0, const float (&x)[16]) __attribute__((always_inline)) {
+      float mx;
+      stats(mt, key0, x, mx);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mxs[mt][i] = fmaxf(mxs[mt][i], x[i]);
+    });
+    prefetch(c_lo, c_hi);                             // the second walk starts where the first did
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mxl[mt * 32 + l32][(wv * 2 + half) * 16 + i] = mxs[mt][i];
+    __syncthreads();
+    const int grow = wv * RPW + (lane >> 3), gl = lane & 7;   // between chunks: 8 lanes look after one row
+    float nb0;
+    {
+      uint32_t keys[kQkSubsets / 8];
+#pragma unroll
+      for (int j = 0; j < kQkSubsets / 8; ++j) keys[j] = float_key(mxl[grow][gl + 8 * j]);
+      nb0 = grow < nrows ? bound_from_key(group_kth(keys, std::integral_constant<int, kQkSubsets / 8>{})) : INFINITY;
     }
+    __syncthreads();                                  // the maxima have been read: the lists may fill
+    if (gl == 0) S.bound[grow] = nb0;
+    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) bound[mt] = mt * 32 + l32 < nrows ? S.bound[mt * 32 + l32] : INFINITY;
+    // second walk: collect
+    walk(c_lo, c_hi, true, [&](int mt, int key0, const float (&x)[16]) __attribute__((always_inline)) {
+      float mx = x[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+      collect(mt, key0, x, mx);
+    });
+  }
+  for (;;) {
+    // the next chunk: at most half as many keys as came before, in whole stripes; its first
+    // sub-tile is requested before the waves meet
+    const int n_lo = c_hi, n_hi = min(n, n_lo + max(kQkStripe, n_lo / 2 / kQkStripe * kQkStripe));
+    if (n_lo < n) prefetch(n_lo, n_hi);
     // every list now holds all logits so far that are at or above the row's bound, hence the K
     // largest: their K-th largest is the new bound, and the entries below it are dropped
-    for (int rr = wv * RPW; rr < wv * RPW + RPW; ++rr) {
-      const uint32_t c = min(S.cnt[rr], (uint32_t)kQkCand);
-      const bool v0 = lane < (int)c, v1 = lane + 64 < (int)c;
-      const uint32_t tkey = kth_key(float_key(S.cand_x[rr][lane]), v0, float_key(S.cand_x[rr][lane + 64]), v1);
+    __syncthreads();
+    {
+      const int grow = wv * RPW + (lane >> 3), gl = lane & 7;
+      const uint32_t c = min(S.cnt[grow], (uint32_t)kQkCand);
+      uint32_t keys[kQkCand / 8];
+#pragma unroll
+      for (int j = 0; j < kQkCand / 8; ++j) keys[j] = gl + 8 * j < (int)c ? float_key(S.cand_x[grow][gl + 8 * j]) : 0u;
+      const uint32_t tkey = group_kth(keys, std::integral_constant<int, kQkCand / 8>{});
       // (a list shorter than K cannot happen for a row of finite logits; -inf keeps everything)
-      const float nb = rr < nrows ? (c >= (uint32_t)topk ? key_to_float(tkey) : -INFINITY) : INFINITY;
-      refilter(rr, nb);
+      const float nbg = grow < nrows ? (c >= (uint32_t)topk ? bound_from_key(tkey) : -INFINITY) : INFINITY;
+      for (int j = 0; j < RPW; ++j) refilter(wv * RPW + j, __shfl(nbg, 8 * j, 64));
     }
     __syncthreads();
-    bound = row_ok ? S.bound[r] : INFINITY;
+    if (c_hi >= n) break;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) bound[mt] = mt * 32 + l32 < nrows ? S.bound[mt * 32 + l32] : INFINITY;
+    c_lo = n_lo;
+    c_hi = n_hi;
+    walk(c_lo, c_hi, true, [&](int mt, int key0, const float (&x)[16]) __attribute__((always_inline)) {
+      float mx;
+      stats(mt, key0, x, mx);
+      collect(mt, key0, x, mx);
+    });
   }
 
-  // statistics of a row: its 8 lanes -> log-sum-exp and needle mass
-  S.st_m[r][ks * 2 + half] = m_run;
-  S.st_s[r][ks * 2 + half] = s_run;
-  S.st_t[r][ks * 2 + half] = t_run;
+  // statistics of a row: its 16 lanes -> log-sum-exp and needle mass
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt) {
+    S.st_m[mt * 32 + l32][wv * 2 + half] = m_run[mt];
+    S.st_s[mt * 32 + l32][wv * 2 + half] = s_run[mt];
+    S.st_t[mt * 32 + l32][wv * 2 + half] = t_run[mt];
+  }
   __syncthreads();
   for (int rr = wv * RPW; rr < min(wv * RPW + RPW, nrows); ++rr) {
     float M = S.st_m[rr][0];
 #pragma unroll
-    for (int j = 1; j < 8; ++j) M = fmaxf(M, S.st_m[rr][j]);
+    for (int j = 1; j < 2 * kQkWaves; ++j) M = fmaxf(M, S.st_m[rr][j]);
     float ssum = 0.f, tsum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < 2 * kQkWaves; ++j) {
       const float f = __builtin_amdgcn_exp2f(S.st_m[rr][j] - M);
       ssum += S.st_s[rr][j] * f;
       tsum += S.st_t[rr][j] * f;
