@@ -64,6 +64,19 @@ def test_rows_of_equal_logits_go_through_the_fallback():
     np.testing.assert_allclose(got[0, 0, :3], [3 * 8 / 1500, 3 * 8 / 1500, 3 * 8 / 1500], rtol=1e-6)
 
 
+def test_logits_rising_along_the_context_overflow_into_the_fallback():
+    # keys of the first KV head = (j / n) * v: rows with q.v > 0 see logits that rise with the position, so every
+    # chunk of keys beats the bound taken from the chunks before it and the candidate lists overflow; rows with
+    # q.v < 0 have their top-K at the very beginning
+    x = wl.config4_qk(L=1, Hq=8, Hkv=2, T=8, n=6000 + 13, d=128, needle_len=16, seed_extra=4)
+    n = x.k.shape[2]
+    v = np.random.default_rng(9).standard_normal(128).astype(np.float32)
+    ramp = (np.arange(n, dtype=np.float32) / n * 6.0)[:, None] * v[None, :]
+    x.k[0, 0] = wl.to_bf16_bits(ramp)
+    x.needle_start = n - 40
+    check(x)
+
+
 def test_needle_run_shape_sampled_heads():
     # the shape bench.py times (32 layers x 32 query / 8 KV heads, 16 steps, 16384 keys); the oracle takes sampled heads
     x = wl.config4_qk()
