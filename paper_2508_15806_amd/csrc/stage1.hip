@@ -386,7 +386,7 @@ __global__ void head_reduce_kernel(const double* __restrict__ cells, int32_t hea
 // its list (the K-th largest logit so far, resolved to its leading bits) and the list is cut back
 // to the entries at or above it; since a chunk holds at most half as many keys as came before, about K/2 new entries
 // join the K carried ones.  Only the first chunk, which has no bound to start from, is walked
-// twice: its first walk tracks 16 running maxima per lane and row, the 16 lanes of a row give 256
+// twice: its first walk tracks 8 running maxima per lane and row, the 16 lanes of a row give 128
 // maxima of disjoint key subsets, and their K-th largest is a lower bound of the row's K-th
 // largest logit; its second walk collects.  So the keys are read 1 + kQkFirst/n times.
 // At the end a wave per row ranks its candidates exactly (larger logit first, equal logits by
@@ -398,7 +398,7 @@ constexpr int kQkWaves = kQkThreads / 64;
 constexpr int kQkRows = 64;          // two row tiles of 32
 constexpr int kQkStripe = 32 * kQkWaves;   // keys the waves take together: chunk ends are multiples of it
 constexpr int kQkFirst = 4 * kQkStripe;    // keys of the first chunk
-constexpr int kQkSubsets = kQkWaves * 2 * 16;   // key subsets per row whose maxima are tracked in the first walk
+constexpr int kQkSubsets = kQkWaves * 2 * 8;    // key subsets per row whose maxima are tracked in the first walk
 constexpr int kQkCand = 128;
 constexpr int kQkBoundBits = 18;     // leading key bits that the bound of a row is resolved to between chunks
 constexpr int kQkFallbackWGs = 128;
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
   static_assert(sizeof(float) * kQkSubsets <= sizeof(S.cand_x[0]) + sizeof(S.cand_p[0]) &&
                     offsetof(QkLds<DK>, cand_p) == sizeof(S.cand_x),
                 "the subset maxima of the first walk live in the (still empty) candidate lists");
-  static_assert(kQkSubsets == 256 && kQkCand == 128 && kQkRows % kQkWaves == 0, "a lane holds four maxima / two candidates of a row");
+  static_assert(kQkSubsets == 128 && kQkCand == 128 && kQkRows % kQkWaves == 0, "eight lanes hold the maxima / candidates of a row, 16 each");
   float (*mxl)[kQkSubsets] = reinterpret_cast<float (*)[kQkSubsets]>(&S.cand_x[0][0]);
   constexpr int RPW = kQkRows / kQkWaves;            // rows a wave looks after between the chunks
   const int G = Hq / Hkv, R = G * T;
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
       qreg[mt][kk] = p.b;
     }
   float m_run[2] = {-INFINITY, -INFINITY}, s_run[2] = {0.f, 0.f}, t_run[2] = {0.f, 0.f};   // running maximum, sum of exp2(x - max), the same over the needle
-  float bound[2] = {INFINITY, INFINITY};
+  float bound[2] = {INFINITY, INFINITY}, bound_raw[2] = {INFINITY, INFINITY};
   __syncthreads();
 
   // one sub-tile of 32 keys starting at key_s: 16 bytes of key row (key_s + l32) per load (clamped at the end of the keys)
@@ -483,88 +483,141 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) kf[kk] = *reinterpret_cast<const qk_u32x4*>(kbase + (off + (uint32_t)kk * 32u));
   };
-  // logits of the sub-tile against both row tiles; body(mt, key0, x): lane's row mt*32 + l32, keys key0 + 8*(i/4) + i%4
-  auto sub_tile = [&](int key_s, const qk_u32x4 (&kf)[KK], auto body) __attribute__((always_inline)) {
-    qk_f32x16 acc[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+  // MFMAs of one sub-tile against both row tiles: acc[mt][i] = q(row mt*32 + l32) . k(key_s + 8*(i/4) + 4*half + i%4),
+  // not yet scaled by log2(e)/sqrt(d)
+  auto mfma_sub = [&](const qk_u32x4 (&kf)[KK], qk_f32x16 (&acc)[2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       QkPack16 p;
       p.u = kf[kk];
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[0][kk], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[1][kk], acc[1], 0, 0, 0);
-    }
-    const int key0 = key_s + 4 * half;
+      if (kk == 0) {
+        qk_f32x16 z;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      float x[16];
-      if (key_s + 32 > n) {                           // the last sub-tile of the keys: mask what lies beyond
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = key0 + 8 * (i >> 2) + (i & 3) < n ? acc[mt][i] * c_log2 : -INFINITY;
+        for (int i = 0; i < 16; ++i) z[i] = 0.f;
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[0][kk], z, 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[1][kk], z, 0, 0, 0);
       } else {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = acc[mt][i] * c_log2;
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[0][kk], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p.b, qreg[1][kk], acc[1], 0, 0, 0);
       }
-      body(mt, key0, x);
     }
   };
-  // this wave's sub-tiles of [key_lo, key_hi) (multiples of kQkStripe, key_hi clipped to n), two in flight
+  // the last sub-tile of the keys: what lies beyond them counts as -inf
+  auto mask_sub = [&](int key_s, qk_f32x16 (&acc)[2]) __attribute__((always_inline)) {
+    if (key_s + 32 > n) {
+      const int key0 = key_s + 4 * half;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (key0 + 8 * (i >> 2) + (i & 3) >= n) acc[mt][i] = -INFINITY;
+    }
+  };
+  // softmax statistics of the 16 unscaled logits a of row tile mt; returns their maximum.  Straight-line
+  // code (it is scheduled among the MFMAs of the next sub-tile); the needle mass of the few sub-tiles
+  // that touch the needle is added by needle_mass() afterwards.
+  auto stats = [&](int mt, const qk_f32x16& a) __attribute__((always_inline)) {
+    float mxr = fmaxf(a[0], a[1]);
+#pragma unroll
+    for (int i = 2; i < 16; i += 2) mxr = fmaxf(mxr, fmaxf(a[i], a[i + 1]));
+    const float mn = fmaxf(m_run[mt], mxr * c_log2);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    const float scale = __builtin_amdgcn_exp2f(m_run[mt] - mu);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(a[i], c_log2, -mu));
+    s_run[mt] = s_run[mt] * scale + sum;
+    t_run[mt] = t_run[mt] * scale;
+    m_run[mt] = mn;
+    return mxr;
+  };
+  // after stats(): the weights of the sub-tile's needle keys, against the same (updated) reference
+  auto needle_mass = [&](int mt, int key0, const qk_f32x16& a) __attribute__((always_inline)) {
+    if (key0 + 32 > needle_start && key0 < ne) {
+      const float mu = m_run[mt] == -INFINITY ? 0.f : m_run[mt];
+      float tsum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = key0 + 8 * (i >> 2) + (i & 3);
+        if (key >= needle_start && key < ne) tsum += __builtin_amdgcn_exp2f(fmaf(a[i], c_log2, -mu));
+      }
+      t_run[mt] += tsum;
+    }
+  };
+  // the logits at or above the bound join the row's list (mxr: the largest unscaled logit of the 16;
+  // bound_raw: the bound in unscaled units, rounded down, so the first test never misses one)
+  auto collect = [&](int mt, int key0, const qk_f32x16& a, float mxr) __attribute__((always_inline)) {
+    if (mxr >= bound_raw[mt]) {
+      const int r = mt * 32 + l32;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float x = a[i] * c_log2;
+        if (x >= bound[mt]) {
+          const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
+          if (slot < (uint32_t)kQkCand) {
+            S.cand_x[r][slot] = x;
+            S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
+          }
+        }
+      }
+    }
+  };
+  // This wave's sub-tiles of [key_lo, key_hi) (multiples of kQkStripe, key_hi clipped to n) as a
+  // software pipeline: the MFMAs of a sub-tile are issued among the statistics of the sub-tile
+  // before it (the two sets of accumulators alternate), and the loads of the sub-tile after it are
+  // in flight.  front(mt, key0, a) runs inside that mix and returns a value that back(mt, key0, a, v)
+  // receives afterwards (back may branch).
   // (preloaded: the wave's first sub-tile is already on its way into kfA, requested by prefetch())
   qk_u32x4 kfA[KK], kfB[KK];
   auto prefetch = [&](int key_lo, int key_hi) __attribute__((always_inline)) {
     if (key_lo + wv * 32 < key_hi) issue(key_lo + wv * 32, kfA);
   };
-  auto walk = [&](int key_lo, int key_hi, bool preloaded, auto body) __attribute__((always_inline)) {
+  auto walk = [&](int key_lo, int key_hi, bool preloaded, auto front, auto back) __attribute__((always_inline)) {
     int ks = key_lo + wv * 32;
-    if (!preloaded && ks < key_hi) issue(ks, kfA);
-    for (; ks < key_hi; ks += 2 * kQkStripe) {
-      const int kb = ks + kQkStripe;
-      if (kb < key_hi) issue(kb, kfB);
-      sub_tile(ks, kfA, body);
-      if (kb + kQkStripe < key_hi) issue(kb + kQkStripe, kfA);
-      if (kb < key_hi) sub_tile(kb, kfB, body);
-    }
-  };
-  // softmax statistics and needle mass of 16 logits of row tile mt
-  auto stats = [&](int mt, int key0, const float (&x)[16], float& mx) __attribute__((always_inline)) {
-    mx = x[0];
+    if (ks >= key_hi) return;
+    if (!preloaded) issue(ks, kfA);
+    qk_f32x16 accA[2], accB[2];
+    if (ks + kQkStripe < key_hi) issue(ks + kQkStripe, kfB);
+    mfma_sub(kfA, accA);
+    // one pipelined step: the sub-tile at ks is in `cur`; the next one goes from kn into `nxt`, and kc is refilled
+    auto pstep = [&](qk_f32x16 (&cur)[2], qk_f32x16 (&nxt)[2], qk_u32x4 (&kc)[KK], qk_u32x4 (&kn)[KK]) __attribute__((always_inline)) {
+      const int key0 = ks + 4 * half;
+      float v[2];
+      // kc held the current sub-tile, whose MFMAs have been issued: refill it with the sub-tile after the next
+      if (ks + 2 * kQkStripe < key_hi) issue(ks + 2 * kQkStripe, kc);
+      mfma_sub(kn, nxt);
+      v[0] = front(0, key0, cur[0]);
+      v[1] = front(1, key0, cur[1]);
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-    const float mn = fmaxf(m_run[mt], mx);
-    const float mu = mn == -INFINITY ? 0.f : mn;
-    const float scale = __builtin_amdgcn_exp2f(m_run[mt] - mu);
-    float sum = 0.f, tsum = 0.f;
-    const bool near_needle = key0 + 32 > needle_start && key0 < ne;     // wave-uniform up to `half`
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float e = __builtin_amdgcn_exp2f(x[i] - mu);
-      sum += e;
-      if (near_needle) {
-        const int key = key0 + 8 * (i >> 2) + (i & 3);
-        tsum += (key >= needle_start && key < ne) ? e : 0.f;
+      for (int g = 0; g < 2 * KK; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);   // eight vector instructions of the statistics
       }
+      // the statistics are complete here (they must not sink below the branches that follow)
+      asm volatile("" ::"v"(v[0]), "v"(v[1]), "v"(s_run[0]), "v"(s_run[1]), "v"(m_run[0]), "v"(m_run[1]));
+      back(0, key0, cur[0], v[0]);
+      back(1, key0, cur[1], v[1]);
+      ks += kQkStripe;
+    };
+    // the wave's last sub-tile of the walk (the only one that can reach past the end of the keys)
+    auto last = [&](qk_f32x16 (&cur)[2]) __attribute__((always_inline)) {
+      const int key0 = ks + 4 * half;
+      mask_sub(ks, cur);
+      const float v0 = front(0, key0, cur[0]), v1 = front(1, key0, cur[1]);
+      back(0, key0, cur[0], v0);
+      back(1, key0, cur[1], v1);
+    };
+    int rem = (key_hi - ks + kQkStripe - 1) / kQkStripe;   // sub-tiles of this wave still to finish (>= 1); the current one is in accA
+    while (rem >= 3) {
+      pstep(accA, accB, kfA, kfB);
+      pstep(accB, accA, kfB, kfA);
+      rem -= 2;
     }
-    s_run[mt] = s_run[mt] * scale + sum;
-    t_run[mt] = t_run[mt] * scale + tsum;
-    m_run[mt] = mn;
-  };
-  // the logits at or above the bound join the row's list (mx: the largest of the 16)
-  auto collect = [&](int mt, int key0, const float (&x)[16], float mx) __attribute__((always_inline)) {
-    if (mx >= bound[mt]) {
-      const int r = mt * 32 + l32;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (x[i] >= bound[mt]) {
-          const uint32_t slot = atomicAdd(&S.cnt[r], 1u);
-          if (slot < (uint32_t)kQkCand) {
-            S.cand_x[r][slot] = x[i];
-            S.cand_p[r][slot] = key0 + 8 * (i >> 2) + (i & 3);
-          }
-        }
-      }
+    if (rem == 2) {
+      pstep(accA, accB, kfA, kfB);
+      last(accB);
+    } else {
+      last(accA);
     }
   };
   // Bounds of the wave's RPW = 8 rows at once: 8 lanes per row, NE keys per lane (0 = no entry).
@@ -622,25 +675,38 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
     }
   };
 
+  // this lane's bounds from the rows' bounds in LDS; the unscaled form is lowered by a few ulps so
+  // that a logit whose scaled value reaches the bound never fails the first test
+  auto load_bounds = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      bound[mt] = mt * 32 + l32 < nrows ? S.bound[mt * 32 + l32] : INFINITY;
+      const float raw = bound[mt] / c_log2;
+      bound_raw[mt] = fabsf(raw) == INFINITY ? raw : raw - fabsf(raw) * 4.8e-7f;
+    }
+  };
+  auto no_front = [&](int, int, const qk_f32x16&) __attribute__((always_inline)) { return 0.f; };
+
   int c_lo = 0, c_hi = min(n, kQkFirst);
   {
-    // The first chunk, first walk: statistics and 16 running maxima per lane and row
-    float mxs[2][16];
+    // The first chunk, first walk: statistics and 8 running maxima (of pairs of keys) per lane and row
+    float mxs[2][8];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mxs[mt][i] = -INFINITY;
-    walk(c_lo, c_hi, false, [&](int mt, int key0, const float (&x)[16]) __attribute__((always_inline)) {
-      float mx;
-      stats(mt, key0, x, mx);
+      for (int i = 0; i < 8; ++i) mxs[mt][i] = -INFINITY;
+    walk(c_lo, c_hi, false,
+         [&](int mt, int, const qk_f32x16& a) __attribute__((always_inline)) { return stats(mt, a); },
+         [&](int mt, int key0, const qk_f32x16& a, float) __attribute__((always_inline)) {
+           needle_mass(mt, key0, a);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mxs[mt][i] = fmaxf(mxs[mt][i], x[i]);
-    });
+           for (int i = 0; i < 8; ++i) mxs[mt][i] = fmaxf(mxs[mt][i], fmaxf(a[2 * i], a[2 * i + 1]));
+         });
     prefetch(c_lo, c_hi);                             // the second walk starts where the first did
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mxl[mt * 32 + l32][(wv * 2 + half) * 16 + i] = mxs[mt][i];
+      for (int i = 0; i < 8; ++i) mxl[mt * 32 + l32][(wv * 2 + half) * 8 + i] = mxs[mt][i] * c_log2;
     __syncthreads();
     const int grow = wv * RPW + (lane >> 3), gl = lane & 7;   // between chunks: 8 lanes look after one row
     float nb0;
@@ -653,15 +719,15 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
     __syncthreads();                                  // the maxima have been read: the lists may fill
     if (gl == 0) S.bound[grow] = nb0;
     __syncthreads();
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) bound[mt] = mt * 32 + l32 < nrows ? S.bound[mt * 32 + l32] : INFINITY;
+    load_bounds();
     // second walk: collect
-    walk(c_lo, c_hi, true, [&](int mt, int key0, const float (&x)[16]) __attribute__((always_inline)) {
-      float mx = x[0];
+    walk(c_lo, c_hi, true, no_front,
+         [&](int mt, int key0, const qk_f32x16& a, float) __attribute__((always_inline)) {
+           float mxr = fmaxf(a[0], a[1]);
 #pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-      collect(mt, key0, x, mx);
-    });
+           for (int i = 2; i < 16; i += 2) mxr = fmaxf(mxr, fmaxf(a[i], a[i + 1]));
+           collect(mt, key0, a, mxr);
+         });
   }
   for (;;) {
     // the next chunk: at most half as many keys as came before, in whole stripes; its first
@@ -684,15 +750,15 @@ __global__ __launch_bounds__(kQkThreads) void qk_cells_kernel(const uint16_t* __
     }
     __syncthreads();
     if (c_hi >= n) break;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) bound[mt] = mt * 32 + l32 < nrows ? S.bound[mt * 32 + l32] : INFINITY;
+    load_bounds();
     c_lo = n_lo;
     c_hi = n_hi;
-    walk(c_lo, c_hi, true, [&](int mt, int key0, const float (&x)[16]) __attribute__((always_inline)) {
-      float mx;
-      stats(mt, key0, x, mx);
-      collect(mt, key0, x, mx);
-    });
+    walk(c_lo, c_hi, true,
+         [&](int mt, int, const qk_f32x16& a) __attribute__((always_inline)) { return stats(mt, a); },
+         [&](int mt, int key0, const qk_f32x16& a, float mxr) __attribute__((always_inline)) {
+           needle_mass(mt, key0, a);
+           collect(mt, key0, a, mxr);
+         });
   }
 
   // statistics of a row: its 16 lanes -> log-sum-exp and needle mass
