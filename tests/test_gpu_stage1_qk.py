@@ -47,6 +47,14 @@ def test_partial_row_group_head_dim_64_small_k():
     check(x)
 
 
+@pytest.mark.parametrize("n,topk,d", [(40, 8, 128), (257, 16, 64), (1024, 64, 128), (1025, 1, 128), (5000, 64, 128)])
+def test_short_contexts_and_the_largest_k(n, topk, d):
+    # fewer keys than one stripe of sub-tiles, exactly the first chunk, one key more, K = 1 and the largest K
+    x = wl.config4_qk(L=1, Hq=4, Hkv=2, T=7, n=n, d=d, needle_len=min(16, n // 2), seed_extra=10 + n)
+    x.topk = topk
+    check(x)
+
+
 def test_several_row_groups_and_accumulation():
     import torch
     x = wl.config4_qk(L=1, Hq=8, Hkv=1, T=12, n=3000, d=128, seed_extra=2)      # 96 rows per KV head: 64 + 32
