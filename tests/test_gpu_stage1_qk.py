@@ -37,7 +37,7 @@ def check(x):
 
 
 def test_one_row_group_ragged_context():
-    # 64 rows per KV head (4 query heads x 16 steps); n is no multiple of the 64-key tile or the super-chunk
+    # 64 rows per KV head (4 query heads x 16 steps); n is no multiple of the 32-key sub-tile or of a stripe of them
     check(wl.config4_qk(L=2, Hq=8, Hkv=2, T=16, n=4096 + 37, d=128))
 
 
