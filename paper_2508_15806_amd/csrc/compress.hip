@@ -253,11 +253,8 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int key = min(key0 + i * (256 / CPR), key_end - 1);
-#ifndef SLKV_NT_MODE
-#define SLKV_NT_MODE 3
-#endif
-      const u32x4* src = reinterpret_cast<const u32x4*>(kbase + ((uint32_t)key * row_bytes + piece_off));
-      pf[i] = ((SLKV_NT_MODE >> (PASS - 1)) & 1) ? __builtin_nontemporal_load(src) : *src;
+      // non-temporal: a workgroup reads its keys once (plain loads measured the same in either pass)
+      pf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase + ((uint32_t)key * row_bytes + piece_off)));
     }
   };
   auto store_tile = [&](const u32x4 (&pf)[LPT], int buf) __attribute__((always_inline)) {
