@@ -49,7 +49,10 @@ typedef enum {
   SLKV_ERR_HIP = 7          /* a HIP call failed (kernel launch) */
 } slkv_status;
 
-typedef enum { SLKV_F32 = 0, SLKV_BF16 = 1, SLKV_F16 = 2 } slkv_dtype;   /* element type of Q, K and V */
+/* Element type of Q, K and V.  SLKV_BF16_KV_FP8: queries bfloat16, keys and values 8-bit floating
+ * point in the OCP E4M3 encoding (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals,
+ * no infinities, S.1111.111 = NaN), one byte per element; strides of d_k / d_v count bytes then. */
+typedef enum { SLKV_F32 = 0, SLKV_BF16 = 1, SLKV_F16 = 2, SLKV_BF16_KV_FP8 = 3 } slkv_dtype;
 typedef enum { SLKV_POOL_NONE = 0, SLKV_POOL_MAX = 1, SLKV_POOL_AVG = 2 } slkv_pool;
 typedef enum { SLKV_BUDGET_EXACT = 0, SLKV_BUDGET_PAPER_LITERAL = 1, SLKV_BUDGET_EXACT_PER_QUERY_HEAD = 2 } slkv_budget_mode;
 
@@ -182,8 +185,8 @@ int32_t slkv_fixed_from_beta(int32_t avg_budget, double beta);
  */
 typedef struct {
   uint32_t struct_size;       /* sizeof(slkv_layer_desc) */
-  int32_t dtype;              /* slkv_dtype of Q, K, V: fp32 (plain FMA kernels), bf16 or fp16 (MFMA kernels,
-                                 products exact in the fp32 accumulators) */
+  int32_t dtype;              /* slkv_dtype of Q, K, V: fp32 (plain FMA kernels), bf16, fp16, or bf16 queries with
+                                 E4M3 keys and values (MFMA kernels, products exact in the fp32 accumulators) */
   int32_t B, Hq, Hkv, d, w;   /* d in {64, 128}; w >= 1; Hq % Hkv == 0; (Hq/Hkv)*w <= 512 */
   int32_t pool_kernel;        /* odd, 1..63; 1 = no pooling */
   int32_t pool;               /* slkv_pool */

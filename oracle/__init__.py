@@ -22,6 +22,7 @@ no worked example (pinned by brute force only).
 
 from .compress import (  # noqa: F401
     bf16_bits_to_f64,
+    fp8_e4m3_to_f64,
     window_importance,
     pool_1d,
     select_topk,

@@ -30,14 +30,28 @@ POOL_MAX = 1
 POOL_AVG = 2
 
 
+def fp8_e4m3_to_f64(b):
+    """OCP 8-bit floating point E4M3 (bytes, uint8) -> float64: 1 sign, 4 exponent (bias 7), 3 mantissa
+    bits; exponent 0 = subnormal (m * 2^-9); no infinities; exponent 15 with mantissa 7 = NaN."""
+    b = np.asarray(b, dtype=np.uint8).astype(np.int64)
+    sign = np.where(b >> 7, -1.0, 1.0)
+    e = (b >> 3) & 15
+    m = (b & 7).astype(np.float64)
+    mag = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    mag = np.where((e == 15) & ((b & 7) == 7), np.nan, mag)
+    return sign * mag
+
+
 def bf16_bits_to_f64(a):
-    """Exact widening of bfloat16 bit patterns (uint16), fp16 or fp32 values to float64."""
+    """Exact widening to float64 of bfloat16 bit patterns (uint16), E4M3 bytes (uint8), fp16 or fp32 values."""
     a = np.asarray(a)
+    if a.dtype == np.uint8:
+        return fp8_e4m3_to_f64(a)
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     if a.dtype == np.float16 or a.dtype == np.float32 or a.dtype == np.float64:
         return a.astype(np.float64)
-    raise TypeError("expected float32, float16 or uint16 (bf16 bits), got %s" % a.dtype)
+    raise TypeError("expected float32, float16, uint16 (bf16 bits) or uint8 (E4M3 bytes), got %s" % a.dtype)
 
 
 def window_importance(q_group, k_hist):

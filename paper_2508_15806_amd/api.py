@@ -7,11 +7,19 @@ import torch
 from . import binding as B
 
 
-DTYPES = {"f32": (B.SLKV_F32, torch.float32), "bf16": (B.SLKV_BF16, torch.bfloat16), "f16": (B.SLKV_F16, torch.float16)}
+# name -> (slkv_dtype, torch dtype of the queries, torch dtype of keys and values)
+DTYPES = {"f32": (B.SLKV_F32, torch.float32, torch.float32), "bf16": (B.SLKV_BF16, torch.bfloat16, torch.bfloat16),
+          "f16": (B.SLKV_F16, torch.float16, torch.float16),
+          "bf16_kv8": (B.SLKV_BF16_KV_FP8, torch.bfloat16, torch.uint8)}   # E4M3 bytes travel as uint8
 
 
 def to_device(arr, dtype, device="cuda"):
-    """numpy fp32 / fp16 array, or uint16 array of bfloat16 bit patterns -> device tensor."""
+    """numpy fp32 / fp16 array, uint16 array of bfloat16 bit patterns or uint8 array of E4M3 bytes -> device tensor."""
+    if dtype == "bf16_kv8":
+        arr = np.ascontiguousarray(arr)
+        if arr.dtype == np.uint8:
+            return torch.from_numpy(arr).to(device)
+        dtype = "bf16"
     if dtype == "bf16":
         t = torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).to(device)
         return t.view(torch.bfloat16)
@@ -39,7 +47,7 @@ class LayerCall:
         self.layer = B.Layer(DTYPES[dtype][0], B_, Hq, Hkv, d, w, cu_seqlens,
                              budgets, k_strides or (d, T * d), v_strides or (d, T * d), pool_kernel, pool)
         self.offsets, self.total_kept = B.slkv_compacted_sizes(self.layer)
-        tdt = DTYPES[dtype][1]
+        tdt = DTYPES[dtype][2]
         rows = max(self.total_kept, 1)
         self.k_out = torch.empty((rows, d), dtype=tdt, device=device)
         self.v_out = torch.empty((rows, d), dtype=tdt, device=device)
@@ -65,7 +73,7 @@ class RaggedCall:
         self.rag = B.Ragged(DTYPES[dtype][0], B_, Hq, Hkv, d, w, in_offsets, budgets,
                             pool_kernel, pool)
         self.offsets, self.total_kept = B.slkv_recompress_sizes(self.rag)
-        tdt = DTYPES[dtype][1]
+        tdt = DTYPES[dtype][2]
         rows = max(self.total_kept, 1)
         self.k_out = torch.empty((rows, d), dtype=tdt, device=device)
         self.v_out = torch.empty((rows, d), dtype=tdt, device=device)

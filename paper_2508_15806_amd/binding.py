@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libslkv.so")
 
-SLKV_F32, SLKV_BF16, SLKV_F16 = 0, 1, 2
+SLKV_F32, SLKV_BF16, SLKV_F16, SLKV_BF16_KV_FP8 = 0, 1, 2, 3
 SLKV_POOL_NONE, SLKV_POOL_MAX, SLKV_POOL_AVG = 0, 1, 2
 SLKV_BUDGET_EXACT, SLKV_BUDGET_PAPER_LITERAL, SLKV_BUDGET_EXACT_PER_QUERY_HEAD = 0, 1, 2
 SLKV_AGG_MICRO, SLKV_AGG_MACRO = 0, 1

@@ -77,6 +77,7 @@ union Pack16 {
 // 32x32x16 MFMA on eight 16-bit elements per lane and operand: bfloat16, or IEEE half when F16
 // (the registers are typed bf16x8 either way; only the instruction reads them differently).
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 template <bool F16>
 __device__ __forceinline__ f32x16 mfma16(bf16x8 a, bf16x8 b, f32x16 c) {
   if constexpr (F16)
@@ -206,9 +207,9 @@ __device__ __forceinline__ void tile_priority(int t) {
 constexpr int kTileKeys = 64;
 constexpr int kPrefetch = 2;
 
-template <int DK, int MT, int RB, int PASS, bool F16, class TAB>
+template <int DK, int MT, int RB, int PASS, int KIND, class TAB>   // KIND: 0 bf16, 1 fp16, 2 bf16 queries with E4M3 keys
 __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(const TAB tab, const uint16_t* __restrict__ q,
-                                                         const uint16_t* __restrict__ kmat, int64_t k_stride_tok,
+                                                         const void* __restrict__ kmat_v, int64_t k_stride_tok,
                                                          int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                          float c_log2, float* __restrict__ part,
                                                          const float* __restrict__ lse, float* __restrict__ imp,
@@ -217,8 +218,10 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   constexpr int TK = kTileKeys;
   constexpr int NSUB = TK / 32 / KS;       // 32-key sub-tiles per wave per tile
   constexpr int KK = DK / 16;
-  constexpr int ROWB = DK * 2 + 16;        // padded LDS row: conflict-free 16-byte reads down a column
-  constexpr int CPR = DK * 2 / 16;         // 16-byte pieces per key row
+  constexpr int ROWB = DK * 2 + 16;        // padded LDS row (bf16 / fp16 elements): conflict-free 16-byte reads down a column
+  constexpr bool KF8 = KIND == 2;          // keys arrive as E4M3 bytes and are widened to bf16 on their way into LDS
+  constexpr int EB = KF8 ? 1 : 2;          // bytes per key element in memory
+  constexpr int CPR = DK * EB / 16;        // 16-byte pieces per key row in memory
   constexpr int LPT = TK * CPR / 256;      // pieces per thread per tile
   constexpr int NPF = kPrefetch;
   static_assert(TK * CPR % 256 == 0 && LPT < 16, "tile must divide over the workgroup; LPT is or-ed into a wait count");
@@ -241,9 +244,9 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   // tiles are processed in pairs (one per register slot); a surplus tile is fully masked
   const int ntiles = ((key_end - key_begin + TK - 1) / TK + 1) & ~1;
   // uniform 64-bit base of the segment's keys + 32-bit byte offsets (the host checks the range)
-  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(
-      kmat + (int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok);
-  const uint32_t row_bytes = (uint32_t)k_stride_tok * 2u;
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(kmat_v) +
+      ((int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok) * EB;
+  const uint32_t row_bytes = (uint32_t)k_stride_tok * (uint32_t)EB;
   const uint32_t piece_off = (uint32_t)(tid % CPR) * 16u;
   const int piece_row = tid / CPR;
 
@@ -261,7 +264,30 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int idx = i * 256 + tid;
-      *reinterpret_cast<u32x4*>(&ktile[buf][(idx / CPR) * ROWB + (idx % CPR) * 16]) = pf[i];
+      if constexpr (KF8) {
+        // 16 E4M3 bytes -> 16 bf16: the hardware converter gives exact fp32 values (checked against the
+        // format's definition for all 256 codes), whose upper halves are the bf16 patterns
+        u32x4 lo, hi;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)pf[i][j], false);
+          const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)pf[i][j], true);
+          const uint32_t p0 = __builtin_amdgcn_perm(__float_as_uint(a[1]), __float_as_uint(a[0]), 0x07060302u);
+          const uint32_t p1 = __builtin_amdgcn_perm(__float_as_uint(b[1]), __float_as_uint(b[0]), 0x07060302u);
+          if (j < 2) {
+            lo[2 * j] = p0;
+            lo[2 * j + 1] = p1;
+          } else {
+            hi[2 * (j - 2)] = p0;
+            hi[2 * (j - 2) + 1] = p1;
+          }
+        }
+        unsigned char* dst = &ktile[buf][(idx / CPR) * ROWB + (idx % CPR) * 32];
+        *reinterpret_cast<u32x4*>(dst) = lo;
+        *reinterpret_cast<u32x4*>(dst + 16) = hi;
+      } else {
+        *reinterpret_cast<u32x4*>(&ktile[buf][(idx / CPR) * ROWB + (idx % CPR) * 16]) = pf[i];
+      }
     }
   };
   static_assert(NPF == 2, "the tile loop below is written out for two register slots");
@@ -333,9 +359,9 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           if (PASS == 1)
-            acc = mfma16<F16>(kreg[kk], qreg[mt][kk], acc);
+            acc = mfma16<KIND == 1>(kreg[kk], qreg[mt][kk], acc);
           else
-            acc = mfma16<F16>(qreg[mt][kk], kreg[kk], acc);
+            acc = mfma16<KIND == 1>(qreg[mt][kk], kreg[kk], acc);
         }
         if (PASS == 1) {
           // lane: query row mt*32 + l32, keys key0 + 8*(i/4) + 4*half + i%4
@@ -449,9 +475,9 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
           f32x16 z;
 #pragma unroll
           for (int i = 0; i < 16; ++i) z[i] = 0.f;
-          cur[mt] = mfma16<F16>(kc[kk], qreg[mt][kk], z);
+          cur[mt] = mfma16<KIND == 1>(kc[kk], qreg[mt][kk], z);
         } else {
-          cur[mt] = mfma16<F16>(kc[kk], qreg[mt][kk], cur[mt]);
+          cur[mt] = mfma16<KIND == 1>(kc[kk], qreg[mt][kk], cur[mt]);
         }
         if (PREFETCH && mt == MT - 1) lds_read(kn[kk], buf, nsub, kk);
         __builtin_amdgcn_sched_barrier(0);
@@ -1567,28 +1593,28 @@ static void ragged_geometry(const slkv_ragged_desc* d, Geometry& g) {
   }
 }
 
-template <int DK, int MT, int RB, bool F16, class TAB>
+template <int DK, int MT, int RB, int KIND, class TAB>
 static void launch_bf16(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                         uint32_t* tickets) {
   if (pass == 1)
-    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, F16, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
-                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, KIND, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+                       k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
                        lse, tickets);
   else
-    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, F16, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
-                       (const uint16_t*)k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, KIND, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+                       k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
                        lse, tickets);
 }
 
-template <int DK, bool F16, class TAB>
+template <int DK, int KIND, class TAB>
 static void launch_bf16_rows(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                              const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                              uint32_t* tickets) {
-  if (p.R <= 64) launch_bf16<DK, 1, 2, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-  else if (p.R <= 128) launch_bf16<DK, 2, 2, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-  else if (p.R <= 256) launch_bf16<DK, 2, 4, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-  else launch_bf16<DK, 4, 4, F16>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  if (p.R <= 64) launch_bf16<DK, 1, 2, KIND>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else if (p.R <= 128) launch_bf16<DK, 2, 2, KIND>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else if (p.R <= 256) launch_bf16<DK, 2, 4, KIND>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  else launch_bf16<DK, 4, 4, KIND>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
 }
 
 template <class TAB>
@@ -1596,11 +1622,14 @@ static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, con
                          const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                          uint32_t* tickets) {
   if (g.dtype == SLKV_BF16) {
-    if (g.d == 128) launch_bf16_rows<128, false>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-    else launch_bf16_rows<64, false>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    if (g.d == 128) launch_bf16_rows<128, 0>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    else launch_bf16_rows<64, 0>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
   } else if (g.dtype == SLKV_F16) {
-    if (g.d == 128) launch_bf16_rows<128, true>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
-    else launch_bf16_rows<64, true>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    if (g.d == 128) launch_bf16_rows<128, 1>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    else launch_bf16_rows<64, 1>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+  } else if (g.dtype == SLKV_BF16_KV_FP8) {
+    if (g.d == 128) launch_bf16_rows<128, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
+    else launch_bf16_rows<64, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
   SLKV_LAUNCH((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
@@ -1747,7 +1776,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
                         d_importance, d_pooled, d_workspace};
   for (const void* ptr : ptrs)
     if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(SLKV_ERR_BAD_ARG, "device pointer %p not 16-byte aligned", ptr);
-  const int elt = g.dtype == SLKV_F32 ? 4 : 2;
+  const int elt = g.dtype == SLKV_F32 ? 4 : (g.dtype == SLKV_BF16_KV_FP8 ? 1 : 2);   // bytes per element of K and V
   const int64_t S = (int64_t)g.segs.size();
   if (S / g.Hkv * g.Hq * g.w >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "B*Hq*w >= 2^31");
   int64_t total_kept = 0;

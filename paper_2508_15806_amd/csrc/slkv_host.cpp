@@ -36,7 +36,7 @@ int64_t kept_rows(int64_t n, int64_t w, int64_t cap) {
 // Checks of the shape parameters the two descriptors share.
 static slkv_status validate_shape(int32_t dtype, int32_t B, int32_t Hq, int32_t Hkv, int32_t dd, int32_t w,
                                   int32_t pool_kernel, int32_t pool, int32_t reserved, const int32_t* h_budgets) {
-  if (dtype != SLKV_F32 && dtype != SLKV_BF16 && dtype != SLKV_F16) return fail(SLKV_ERR_BAD_ARG, "unknown dtype %d", dtype);
+  if (dtype != SLKV_F32 && dtype != SLKV_BF16 && dtype != SLKV_F16 && dtype != SLKV_BF16_KV_FP8) return fail(SLKV_ERR_BAD_ARG, "unknown dtype %d", dtype);
   if (B < 1 || Hq < 1 || Hkv < 1 || w < 1) return fail(SLKV_ERR_BAD_ARG, "B, Hq, Hkv, w must be >= 1");
   if (B > (1 << 20) || Hkv > (1 << 16) || Hq > (1 << 16)) return fail(SLKV_ERR_BAD_ARG, "B, Hq or Hkv too large");
   if (Hq % Hkv) return fail(SLKV_ERR_BAD_ARG, "Hq %% Hkv != 0");
@@ -67,7 +67,7 @@ slkv_status validate_desc(const slkv_layer_desc* d) {
     if (d->h_cu_seqlens[b + 1] < d->h_cu_seqlens[b]) return fail(SLKV_ERR_BAD_ARG, "cu_seqlens not monotone at %d", b);
   if (d->h_cu_seqlens[d->B] >= (int64_t(1) << 31)) return fail(SLKV_ERR_BAD_ARG, "cu_seqlens[B] >= 2^31");
   const int64_t strides[4] = {d->k_stride_tok, d->k_stride_head, d->v_stride_tok, d->v_stride_head};
-  const int64_t align_elems = d->dtype == SLKV_F32 ? 4 : 8;
+  const int64_t align_elems = d->dtype == SLKV_F32 ? 4 : (d->dtype == SLKV_BF16_KV_FP8 ? 16 : 8);   // 16 bytes
   for (int i = 0; i < 4; ++i) {
     if (strides[i] < 0 || strides[i] % align_elems) return fail(SLKV_ERR_BAD_ARG, "stride %d not a non-negative multiple of %lld elements", i, (long long)align_elems);
   }
@@ -115,7 +115,7 @@ const char* slkv_status_str(slkv_status s) {
 
 const char* slkv_last_error(void) { return g_err; }
 
-int32_t slkv_version(void) { return 1004; }
+int32_t slkv_version(void) { return 1005; }
 
 int32_t slkv_fixed_from_beta(int32_t avg_budget, double beta) {
   if (avg_budget < 0 || !(beta >= 1.0)) return -1;

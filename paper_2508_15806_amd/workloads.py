@@ -36,6 +36,25 @@ def to_bf16_bits(x):
     return (r >> np.uint32(16)).astype(np.uint16)
 
 
+def _e4m3_magnitudes():
+    """The 127 finite non-negative E4M3 values (code = index), ascending."""
+    code = np.arange(127)
+    e, m = code >> 3, code & 7
+    return np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+
+
+def to_fp8_e4m3_bits(x):
+    """fp32 -> OCP E4M3 bytes (uint8): round to nearest, ties to the even code, saturating at 448."""
+    x = np.asarray(x, dtype=np.float32)
+    mags = _e4m3_magnitudes()
+    a = np.minimum(np.abs(x).astype(np.float64), mags[-1])
+    hi = np.clip(np.searchsorted(mags, a, side="left"), 0, 126)
+    lo = np.maximum(hi - 1, 0)
+    dlo, dhi = a - mags[lo], mags[hi] - a
+    code = np.where(dlo < dhi, lo, np.where(dhi < dlo, hi, np.where(lo % 2 == 0, lo, hi)))
+    return (code | (np.signbit(x).astype(np.int64) << 7)).astype(np.uint8)
+
+
 def bf16_bits_to_f32(b):
     return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
@@ -45,7 +64,8 @@ class LayerInputs:
     """One layer's inputs for the compression pass.
 
     qwin [B, Hq, w, d]; k, v [Hkv, T, d] (sequences packed along T);
-    cu_seqlens [B+1] int64.  dtype "f32" (float32 arrays), "f16" (float16 arrays) or "bf16" (uint16 bit
+    cu_seqlens [B+1] int64.  dtype "f32" (float32 arrays), "f16" (float16 arrays), "bf16_kv8" (queries as
+    bf16 bit patterns, keys and values as E4M3 bytes) or "bf16" (uint16 bit
     patterns)."""
     dtype: str
     B: int
@@ -93,8 +113,10 @@ def make_layer(seed_key, seqlens, Hq, Hkv, d, w, dtype="bf16", bias_frac=0.0, bi
         q, k, v = to_bf16_bits(q), to_bf16_bits(k), to_bf16_bits(v)
     elif dtype == "f16":
         q, k, v = q.astype(np.float16), k.astype(np.float16), v.astype(np.float16)
+    elif dtype == "bf16_kv8":
+        q, k, v = to_bf16_bits(q), to_fp8_e4m3_bits(k), to_fp8_e4m3_bits(v)
     elif dtype != "f32":
-        raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
+        raise ValueError("dtype must be 'f32', 'bf16', 'f16' or 'bf16_kv8'")
     return LayerInputs(dtype, B, Hq, Hkv, d, w, cu, q, k, v)
 
 
@@ -145,8 +167,10 @@ def make_ragged_cache(seed_key, seg_lens, B, Hq, Hkv, d, w, dtype="bf16", bias_f
         q, k, v = to_bf16_bits(q), to_bf16_bits(k), to_bf16_bits(v)
     elif dtype == "f16":
         q, k, v = q.astype(np.float16), k.astype(np.float16), v.astype(np.float16)
+    elif dtype == "bf16_kv8":
+        q, k, v = to_bf16_bits(q), to_fp8_e4m3_bits(k), to_fp8_e4m3_bits(v)
     elif dtype != "f32":
-        raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
+        raise ValueError("dtype must be 'f32', 'bf16', 'f16' or 'bf16_kv8'")
     return RaggedCache(dtype, B, Hq, Hkv, d, w, offs, q, k, v, pos)
 
 

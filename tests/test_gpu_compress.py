@@ -82,6 +82,26 @@ def test_fp16_long_history_and_token_major():
     assert rep["ranked"] == 3 and rep["tolerant"] == 0
 
 
+@pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 16, 128), (8, 2, 32, 128), (4, 4, 24, 64), (16, 4, 64, 128), (16, 2, 64, 64)])
+def test_e4m3_keys_and_values_row_shapes(Hq, Hkv, w, d):
+    # bf16 queries against keys / values stored as E4M3 bytes (widened to bf16 inside the kernels, exactly)
+    lay = wl.make_layer((141, Hq, w, d), [1000 + w + 7, 333 + w], Hq, Hkv, d, w, dtype="bf16_kv8", bias_frac=0.03)
+    assert lay.k.dtype == np.uint8 and lay.qwin.dtype == np.uint16
+    bud = np.array([w + 40 + 13 * h for h in range(Hkv)], dtype=np.int32)
+    check(lay, bud)
+
+
+def test_e4m3_every_code_long_history_and_token_major():
+    lay = wl.make_layer((142,), [40000 + 64 + 9, 700], 8, 2, 128, 64, dtype="bf16_kv8", bias_frac=0.02)
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)      # every finite code, subnormals included
+    lay.k[0, :codes.size * 4, :] = np.resize(codes, (codes.size * 4, 128))
+    rep = check(lay, np.array([900, 150], dtype=np.int32))
+    assert rep["ranked"] == 3 and rep["tolerant"] == 0
+    lay = wl.make_layer((143,), [1500 + 11, 0, 260], 8, 4, 128, 16, dtype="bf16_kv8", bias_frac=0.04)
+    rep = check(lay, np.array([300, 16, 90, 2000], dtype=np.int32), token_major=True)
+    assert rep["ranked"] == 3 and rep["tolerant"] == 0
+
+
 @pytest.mark.parametrize("Hq,Hkv,w,d", [(2, 2, 8, 64), (4, 2, 32, 128), (8, 1, 40, 64)])
 def test_fp32_shapes(Hq, Hkv, w, d):
     lay = wl.make_layer((102, Hq, w, d), [700 + w + 5, 90], Hq, Hkv, d, w, dtype="f32", bias_frac=0.03)

@@ -33,7 +33,7 @@ def test_heads_of_different_lengths_bf16():
 
 
 @pytest.mark.parametrize("Hq,Hkv,w,d,dtype", [(4, 2, 8, 64, "f32"), (8, 2, 32, 128, "bf16"), (8, 8, 24, 64, "bf16"),
-                                              (8, 2, 32, 128, "f16")])
+                                              (8, 2, 32, 128, "f16"), (8, 2, 32, 128, "bf16_kv8")])
 def test_shapes(Hq, Hkv, w, d, dtype):
     rng = np.random.default_rng(7)
     lens = rng.integers(w + 1, 900, size=3 * Hkv).tolist()

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert B.slkv_version() == 1004
+    assert B.slkv_version() == 1005
     assert L.slkv_status_str(0) == b"ok"
 
 

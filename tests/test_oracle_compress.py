@@ -120,6 +120,28 @@ def test_fp16_widening_is_exact_and_the_layer_equals_its_fp32_copy():
     assert a["k_out"].dtype == np.float16 and np.array_equal(a["k_out"].astype(np.float32), b["k_out"])
 
 
+def test_e4m3_widening_follows_the_format_and_the_generator_rounds_to_nearest_even():
+    v = oracle.fp8_e4m3_to_f64(np.arange(256, dtype=np.uint8))
+    # bias 7, three mantissa bits, subnormals m * 2^-9, largest finite value 448, S.1111.111 = NaN
+    assert v[0x38] == 1.0 and v[0x39] == 1.125 and v[0x40] == 2.0 and v[0x7E] == 448.0 and v[0x08] == 2.0 ** -6
+    assert v[0x01] == 2.0 ** -9 and v[0x07] == 7 * 2.0 ** -9 and v[0x00] == 0.0 and v[0xB8] == -1.0
+    assert np.isnan(v[0x7F]) and np.isnan(v[0xFF]) and np.isfinite(np.delete(v, [0x7F, 0xFF])).all()
+    assert (np.diff(v[:0x7F]) > 0).all()                      # codes of one sign are ordered like their values
+    x = np.array([1.0625, 1.1875, 2.0 ** -10, 1000.0, -0.3, 0.0], dtype=np.float32)
+    assert wl.to_fp8_e4m3_bits(x).tolist() == [0x38, 0x3A, 0x00, 0x7E, 0xAA, 0x00]      # ties to even, saturation
+    fin = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    assert np.array_equal(wl.to_fp8_e4m3_bits(v[fin].astype(np.float32)) & 0x7F, fin & 0x7F)
+    # a layer with E4M3 keys / values is the same problem as its values stored in fp32
+    lay = wl.make_layer((42,), [300, 77], 4, 2, 64, 16, dtype="bf16_kv8", bias_frac=0.05)
+    bud = np.array([60, 100], dtype=np.int32)
+    a = oracle.compress_layer(lay.qwin, lay.k, lay.v, lay.cu_seqlens, bud, lay.w, 7)
+    b = oracle.compress_layer(oracle.bf16_bits_to_f64(lay.qwin).astype(np.float32), oracle.fp8_e4m3_to_f64(lay.k).astype(np.float32),
+                              oracle.fp8_e4m3_to_f64(lay.v).astype(np.float32), lay.cu_seqlens, bud, lay.w, 7)
+    for sa, sb in zip(a["segments"], b["segments"]):
+        assert np.array_equal(sa["kept_idx"], sb["kept_idx"]) and np.array_equal(sa["importance"], sb["importance"])
+    assert a["k_out"].dtype == np.uint8
+
+
 @pytest.mark.parametrize("kernel", [1, 3, 7, 9])
 def test_max_pool_matches_scipy_and_loop(kernel):
     x = np.random.default_rng(6).random(101)
