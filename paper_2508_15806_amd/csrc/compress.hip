@@ -1128,7 +1128,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   __shared__ uint32_t hist[kHistBins];
   __shared__ int32_t sh_pos[kInlineGatherRows];
   __shared__ uint32_t sh_scan[NT / 64];
-  __shared__ uint32_t res[2];
+  __shared__ uint32_t res[3];                      // [0], [1]: digit search and ranking results; [2]: length of the candidate list
   __shared__ uint32_t sh_mm[2 * (NT / 64)];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -1258,22 +1258,22 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     for (int e = 0; e < EPT; ++e)
       if (j0 + e < m) P[j0 + e] = p[e];
   }
-#pragma unroll
-  for (int dlt = 32; dlt > 0; dlt >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, dlt, 64));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, dlt, 64));
-  }
-  if (lane == 0) {
+  kmin = wave_reduce_to_last(kmin, [](uint32_t a, uint32_t b) { return min(a, b); });
+  kmax = wave_reduce_to_last(kmax, [](uint32_t a, uint32_t b) { return max(a, b); });
+  if (lane == 63) {
     sh_mm[wv] = kmin;
     sh_mm[NT / 64 + wv] = kmax;
   }
+  for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;   // for the first level below
+  if (tid == 0) res[2] = 0;
   __syncthreads();
+  kmin = sh_mm[0];
+  kmax = sh_mm[NT / 64];
 #pragma unroll
-  for (int i = 0; i < NT / 64; ++i) {
+  for (int i = 1; i < NT / 64; ++i) {
     kmin = min(kmin, sh_mm[i]);
     kmax = max(kmax, sh_mm[NT / 64 + i]);
   }
-  __syncthreads();
 
   SLKV_STAMP(128 + seg, 2);
   // Radix select on (key - lo) >> shift.  The first level histograms every score; the scores
@@ -1284,19 +1284,25 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   constexpr uint32_t kCandCap = kResCandidates;
   bool use_list = false;
   uint32_t ncand = 0;
+  const bool full = j0 + EPT <= m;                 // this thread holds no key of a position past the end
   for (int level = 0;; ++level) {
     const uint32_t span1 = hi - lo;
     const int nbits = span1 ? 32 - __clz(span1) : 0;
     const int shift = nbits > 11 ? nbits - 11 : 0;
     if (use_list && ncand <= kSelRankMax) {
-      // short list: the k-th largest by counting, for each entry, the entries above it
+      // short list: the k-th largest by counting, for each entry, the entries above it (four
+      // entries a step; the list's array is longer than any index read here)
       if ((uint32_t)tid < ncand) {
         const uint32_t kv = cand[tid];
         uint32_t gt = 0, ge = 0;
-        for (uint32_t i = 0; i < ncand; ++i) {
-          const uint32_t o = cand[i];
-          gt += o > kv ? 1u : 0u;
-          ge += o >= kv ? 1u : 0u;
+        for (uint32_t i = 0; i < ncand; i += 4) {
+#pragma unroll
+          for (uint32_t u = 0; u < 4; ++u) {
+            const uint32_t o = cand[i + u];
+            const bool live = i + u < ncand;
+            gt += (live && o > kv) ? 1u : 0u;
+            ge += (live && o >= kv) ? 1u : 0u;
+          }
         }
         if (gt < k && k <= ge) {   // every thread holding the k-th largest value writes the same pair
           res[0] = kv;
@@ -1306,16 +1312,22 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       __syncthreads();
       lo = res[0];
       k = res[1];
-      __syncthreads();
       break;
     }
-    for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
-    __syncthreads();
+    if (level > 0) {               // (the first level's histogram was cleared above)
+      __syncthreads();             // every thread has read the counts and results of the level before
+      for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
+      __syncthreads();
+    }
     if (use_list) {
       for (uint32_t i = tid; i < ncand; i += NT) {
         const uint32_t kv = cand[i];
         if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
       }
+    } else if (level == 0 && full) {
+      // lo and hi are the smallest and largest key of the segment: nothing to test
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) atomicAdd(&hist[(key[e] - lo) >> shift], 1u);
     } else {
       // in [lo, hi] <=> key - lo <= hi - lo: a key below lo wraps to a difference above any span,
       // and kKeyNone lies above every hi
@@ -1331,25 +1343,22 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     if (level == 0) SLKV_STAMP(128 + seg, 4);
     const uint32_t bsel = res[0], cnt_sel = hist[bsel];
     k = res[1];
-    __syncthreads();
     lo = lo + (bsel << shift);
     hi = min(hi, lo + ((1u << shift) - 1u));
     if (shift == 0) break;
     if (level == 0 && cnt_sel <= kCandCap) {
-      // collect the scores of the chosen digit (their order does not matter for counting)
-      if (tid == 0) res[0] = 0;
-      __syncthreads();
+      // collect the scores of the chosen digit (their order does not matter for counting); the
+      // results above are not written again before the barrier below
       const uint32_t span2 = hi - lo;
 #pragma unroll
       for (int e = 0; e < EPT; ++e)
         if (key[e] - lo <= span2) {
-          const uint32_t slot = atomicAdd(&res[0], 1u);
+          const uint32_t slot = atomicAdd(&res[2], 1u);
           if (slot < kCandCap) cand[slot] = key[e];
         }
       __syncthreads();
-      ncand = res[0];
+      ncand = res[2];
       use_list = true;
-      __syncthreads();
     }
   }
   const uint32_t tau = lo, need_eq = k;
@@ -1358,15 +1367,19 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   // ordered compaction: slot = (#greater before) + min(#equal before, need_eq)
   {
     uint32_t gmask = 0, emask = 0;                 // bit e: element e is above / equal to the threshold
-    const uint32_t above = kKeyNone - tau - 1u;     // tau < key < kKeyNone <=> key - tau - 1 < above
+    const uint32_t upto = kKeyNone - tau;           // tau <= key < kKeyNone <=> key - tau < upto
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      gmask |= (key[e] - tau - 1u < above) ? (1u << e) : 0u;
-      emask |= key[e] == tau ? (1u << e) : 0u;
+      const uint32_t dk = key[e] - tau;
+      const bool in = dk < upto;
+      if (__builtin_amdgcn_ballot_w64(in)) {        // few positions are kept: most waves skip most steps
+        gmask |= (in && dk != 0u) ? (1u << e) : 0u;
+        emask |= dk == 0u ? (1u << e) : 0u;
+      }
     }
     const uint32_t cg = __popc(gmask), ce = __popc(emask);
     const uint32_t packed = (ce << 16) | cg;       // the round holds at most 32768 of either
-    const uint32_t incl = block_incl_scan<NT, uint32_t>(packed, sh_scan);
+    const uint32_t incl = block_incl_scan<NT, false>(packed, sh_scan);   // sh_scan is not used again
     const uint32_t excl = incl - packed;
     const uint32_t g_before = excl & 0xffffu, e_before = excl >> 16;
     // ties are taken in position order: this thread keeps its first `take` equal elements

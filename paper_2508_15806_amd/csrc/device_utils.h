@@ -10,14 +10,44 @@ namespace slkv {
 constexpr int kWave = 64;
 constexpr int kHistBins = 2048;
 
-template <typename T>
-__device__ __forceinline__ T wave_incl_scan(T v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int dlt = 1; dlt < kWave; dlt <<= 1) {
-    T o = __shfl_up(v, dlt, kWave);
-    if (lane >= dlt) v += o;
-  }
+// One cross-lane move inside the wave (DPP): every lane reads `src` of the lane that the control
+// word CTRL names; a lane whose source lies outside its row of 16, or whose row ROW_MASK leaves
+// out, gets `old` instead.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t old, uint32_t src) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int kDppRowShr = 0x110;       // + n: lane l reads lane l - n of its row
+constexpr int kDppRowBcast15 = 0x142;   // lane 15 of a row goes to every lane of the next row
+constexpr int kDppRowBcast31 = 0x143;   // lane 31 goes to every lane of rows 2 and 3
+
+// Inclusive prefix sums inside each row of 16 lanes.
+__device__ __forceinline__ uint32_t row_incl_scan(uint32_t v) {
+  v += dpp_move<kDppRowShr + 1>(0u, v);
+  v += dpp_move<kDppRowShr + 2>(0u, v);
+  v += dpp_move<kDppRowShr + 4>(0u, v);
+  v += dpp_move<kDppRowShr + 8>(0u, v);
+  return v;
+}
+
+// Inclusive prefix sums over the 64 lanes: the rows first, then the last lane of row 0 and of
+// row 2 is added to the row after it, then the last lane of row 1 to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  v = row_incl_scan(v);
+  v += dpp_move<kDppRowBcast15, 0xa>(0u, v);
+  v += dpp_move<kDppRowBcast31, 0xc>(0u, v);
+  return v;
+}
+
+// op over the 64 lanes for an idempotent op (min, max): the result is valid in lane 63 only.
+template <class OP>
+__device__ __forceinline__ uint32_t wave_reduce_to_last(uint32_t v, OP op) {
+  v = op(v, dpp_move<kDppRowShr + 1>(v, v));
+  v = op(v, dpp_move<kDppRowShr + 2>(v, v));
+  v = op(v, dpp_move<kDppRowShr + 4>(v, v));
+  v = op(v, dpp_move<kDppRowShr + 8>(v, v));
+  v = op(v, dpp_move<kDppRowBcast15, 0xa>(v, v));
+  v = op(v, dpp_move<kDppRowBcast31, 0xc>(v, v));
   return v;
 }
 
@@ -29,22 +59,20 @@ __device__ __forceinline__ T wave_sum(T v) {
 }
 
 // Inclusive scan over the NT threads of the block in thread order.  `sh` holds NT/64 values.
-// Ends with a barrier, so `sh` may be reused at once.
-template <int NT, typename T>
-__device__ __forceinline__ T block_incl_scan(T v, T* sh) {
+// Every wave adds up the totals of the waves before it by itself.  With TRAIL the call ends
+// with a barrier, so `sh` may be reused at once; without, the caller places that barrier.
+template <int NT, bool TRAIL = true>
+__device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* sh) {
   constexpr int NW = NT / kWave;
-  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
-  T s = wave_incl_scan(v);
+  static_assert(NW <= 16, "the wave totals are scanned inside one row of 16 lanes");
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t s = wave_incl_scan(v);
   if (lane == kWave - 1) sh[wv] = s;
   __syncthreads();
-  if (wv == 0) {
-    T t = lane < NW ? sh[lane] : T(0);
-    t = wave_incl_scan(t);
-    if (lane < NW) sh[lane] = t;
-  }
-  __syncthreads();
-  T base = wv ? sh[wv - 1] : T(0);
-  __syncthreads();
+  const uint32_t t = row_incl_scan(lane < NW ? sh[lane] : 0u);
+  const uint32_t base = wv ? (uint32_t)__builtin_amdgcn_readlane((int)t, wv - 1) : 0u;
+  if (TRAIL) __syncthreads();
   return s + base;
 }
 
@@ -77,7 +105,7 @@ __device__ __forceinline__ void select_bin(const uint32_t* hist, uint32_t k, uin
     c[i] = hist[t * BPT + i];
     sum += c[i];
   }
-  const uint32_t incl = block_incl_scan<NT, uint32_t>(sum, sh_scan);
+  const uint32_t incl = block_incl_scan<NT, false>(sum, sh_scan);   // the barrier below covers sh_scan
   uint32_t above = incl - sum;
   if (above < k && incl >= k) {
 #pragma unroll
