@@ -1109,7 +1109,8 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
 // digits relative to the segment's own [min, max] of keys, which spreads the LDS histogram over
 // nearly all bins and leaves few scores in the chosen one.
 constexpr int kResStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * kSelHaloMax) >> 5) + 8;
-constexpr int kResCandidates = 3072;   // scores of one first-level digit that the LDS list can hold
+constexpr int kResCandidates = 3072;   // keys that the list behind the staging array can hold
+constexpr int kResAuxWords = 3 * kHistBins;   // second histogram, largest and smallest key per digit: the start of the staging array, once the scores are in registers
 constexpr size_t kResLdsBytes = (size_t)(kResStageFloats + kResCandidates) * sizeof(float);
 
 // index into the staging array: one word of padding per thread's positions, so that the threads
@@ -1128,7 +1129,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   __shared__ uint32_t hist[kHistBins];
   __shared__ int32_t sh_pos[kInlineGatherRows];
   __shared__ uint32_t sh_scan[NT / 64];
-  __shared__ uint32_t res[3];                      // [0], [1]: digit search and ranking results; [2]: length of the candidate list
+  __shared__ uint32_t res[4];                      // [0], [1]: digit search and ranking results; [2], [3]: list lengths, in turn
   __shared__ uint32_t sh_mm[2 * (NT / 64)];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -1258,14 +1259,25 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     for (int e = 0; e < EPT; ++e)
       if (j0 + e < m) P[j0 + e] = p[e];
   }
+  const uint32_t tmax = kmax;                      // largest key of this thread's own positions
   kmin = wave_reduce_to_last(kmin, [](uint32_t a, uint32_t b) { return min(a, b); });
   kmax = wave_reduce_to_last(kmax, [](uint32_t a, uint32_t b) { return max(a, b); });
   if (lane == 63) {
     sh_mm[wv] = kmin;
     sh_mm[NT / 64 + wv] = kmax;
   }
-  for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;   // for the first level below
-  if (tid == 0) res[2] = 0;
+  // histograms for the levels below, cleared here under the same barrier; the second one and the
+  // digits' largest and smallest keys live at the start of the staging array, which is free now
+  uint32_t* const aux_hist = reinterpret_cast<uint32_t*>(stage);
+  uint32_t* const aux_max = aux_hist + kHistBins;
+  uint32_t* const aux_min = aux_max + kHistBins;
+  for (int i = tid; i < kHistBins; i += NT) {
+    hist[i] = 0;
+    aux_hist[i] = 0;
+    aux_max[i] = 0;
+    aux_min[i] = 0xffffffffu;
+  }
+  if (tid == 0) res[2] = 0;                        // counter of the first list (see below)
   __syncthreads();
   kmin = sh_mm[0];
   kmax = sh_mm[NT / 64];
@@ -1276,30 +1288,123 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   }
 
   SLKV_STAMP(128 + seg, 2);
-  // Radix select on (key - lo) >> shift.  The first level histograms every score; the scores
-  // of the chosen digit are then collected in LDS (the staging array) and the remaining
-  // levels work on that list.  If the list would not fit, the levels sweep all scores again.
+  // The k-th largest key: radix select on (key - lo) >> shift with 11-bit digits taken relative to
+  // the range [lo, hi] still in question.  After a digit search the keys of the chosen digit are
+  // copied to a list in LDS (two areas in turn), the next level histograms that list, and a list of
+  // at most kSelRankMax keys is ranked by direct counting.
+  // Where at least k threads hold positions, two shortcuts come first.  The k-th largest of the
+  // threads' own maxima bounds the k-th largest key from below: its digit is found from a histogram
+  // of one key per thread, and the first level over all keys then counts only those from that
+  // digit's lower edge upwards (a few times k, as a rule), in finer digits.  That level also keeps
+  // the largest and smallest key of every digit: if the chosen digit holds one value only (with
+  // max pooling a run of equal scores, as a rule), or its largest key is the one wanted, the
+  // search ends there.
   uint32_t lo = kmin, hi = kmax, k = (uint32_t)kk;
-  uint32_t* cand = reinterpret_cast<uint32_t*>(stage + kResStageFloats);   // after the staging area
-  constexpr uint32_t kCandCap = kResCandidates;
-  bool use_list = false;
-  uint32_t ncand = 0;
+  auto list_at = [&](int i) { return reinterpret_cast<uint32_t*>(stage) + (i ? kResStageFloats : kResAuxWords); };
+  auto list_cap = [](int i) { return (uint32_t)(i ? kResCandidates : kSelRound - kResAuxWords); };
+  int cur = -1;                                    // the list that holds the candidates; -1: the keys in registers
+  uint32_t nlist = 0;
+  int ncollect = 0;                                // lists made so far; list i counts its entries in res[2 + (i & 1)]
+  bool hist_clean = true, unsynced = false;        // unsynced: results of a digit search read, no barrier since
+  bool pending = false;                            // a digit has been chosen whose keys are not listed yet
+  bool found = false;
+  uint32_t cnt_sel = 0;
   const bool full = j0 + EPT <= m;                 // this thread holds no key of a position past the end
-  for (int level = 0;; ++level) {
+  auto shift_of = [](uint32_t span) {
+    const int nbits = span ? 32 - __clz(span) : 0;
+    return nbits > 11 ? nbits - 11 : 0;
+  };
+  // a list is made between two barriers: the counter of the one after it is cleared meanwhile
+  auto begin_list = [&]() {
+    if (tid == 0) res[2 + ((ncollect + 1) & 1)] = 0;
+  };
+  auto push = [&](int dst, uint32_t kv) __attribute__((always_inline)) {
+    const uint32_t slot = atomicAdd(&res[2 + (ncollect & 1)], 1u);
+    if (slot < list_cap(dst)) list_at(dst)[slot] = kv;
+  };
+  auto end_list = [&](int dst) {
+    __syncthreads();
+    nlist = min(res[2 + (ncollect & 1)], list_cap(dst));
+    ++ncollect;
+    cur = dst;
+    unsynced = false;
+  };
+  const uint32_t owners = (uint32_t)((m + EPT - 1) / EPT);   // threads that hold at least one position
+  if (k <= owners) {
+    {
+      const int shift = shift_of(hi - lo);
+      if ((uint32_t)tid < owners) atomicAdd(&hist[(tmax - lo) >> shift], 1u);
+      __syncthreads();
+      SLKV_STAMP(128 + seg, 3);
+      select_bin<NT>(hist, k, sh_scan, res);
+      SLKV_STAMP(128 + seg, 4);
+      lo += res[0] << shift;                       // k threads hold a key >= lo, so the k-th largest key is >= lo
+      hist_clean = false;
+    }
     const uint32_t span1 = hi - lo;
-    const int nbits = span1 ? 32 - __clz(span1) : 0;
-    const int shift = nbits > 11 ? nbits - 11 : 0;
-    if (use_list && ncand <= kSelRankMax) {
+    const int shift = shift_of(span1);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const uint32_t dk = key[e] - lo;               // (a key below lo wraps to a difference above any span)
+      if (dk <= span1) {
+        const uint32_t d = dk >> shift;
+        atomicAdd(&aux_hist[d], 1u);
+        atomicMax(&aux_max[d], key[e]);
+        atomicMin(&aux_min[d], key[e]);
+      }
+    }
+    __syncthreads();
+    select_bin<NT>(aux_hist, k, sh_scan, res);
+    const uint32_t bsel = res[0];
+    const uint32_t top = aux_max[bsel], bottom = aux_min[bsel];
+    cnt_sel = aux_hist[bsel];
+    k = res[1];
+    unsynced = true;
+    lo = lo + (bsel << shift);
+    hi = min(hi, lo + ((1u << shift) - 1u));
+    if (shift == 0 || top == bottom || k == 1u) {
+      lo = top;                                    // one value in the digit, or the largest of the digit is wanted
+      found = true;
+    } else {
+      pending = true;
+    }
+  }
+  while (!found) {
+    if (pending) {
+      // the keys of the chosen digit go to the other list (their order does not matter for counting)
+      pending = false;
+      const int dst = cur == 0 ? 1 : 0;
+      if (cnt_sel <= list_cap(dst)) {
+        begin_list();
+        const uint32_t span2 = hi - lo;
+        if (cur >= 0) {
+          const uint32_t* cand = list_at(cur);
+          for (uint32_t i = tid; i < nlist; i += NT) {
+            const uint32_t kv = cand[i];
+            if (kv - lo <= span2) push(dst, kv);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPT; ++e)
+            if (key[e] - lo <= span2) push(dst, key[e]);
+        }
+        end_list(dst);
+      }
+    }
+    const uint32_t span1 = hi - lo;
+    const int shift = shift_of(span1);
+    if (cur >= 0 && nlist <= (uint32_t)kSelRankMax) {
       // short list: the k-th largest by counting, for each entry, the entries above it (four
-      // entries a step; the list's array is longer than any index read here)
-      if ((uint32_t)tid < ncand) {
+      // entries a step; both list areas are longer than any index read here)
+      const uint32_t* cand = list_at(cur);
+      if ((uint32_t)tid < nlist) {
         const uint32_t kv = cand[tid];
         uint32_t gt = 0, ge = 0;
-        for (uint32_t i = 0; i < ncand; i += 4) {
+        for (uint32_t i = 0; i < nlist; i += 4) {
 #pragma unroll
           for (uint32_t u = 0; u < 4; ++u) {
             const uint32_t o = cand[i + u];
-            const bool live = i + u < ncand;
+            const bool live = i + u < nlist;
             gt += (live && o > kv) ? 1u : 0u;
             ge += (live && o >= kv) ? 1u : 0u;
           }
@@ -1314,17 +1419,18 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       k = res[1];
       break;
     }
-    if (level > 0) {               // (the first level's histogram was cleared above)
-      __syncthreads();             // every thread has read the counts and results of the level before
+    if (!hist_clean) {
+      if (unsynced) __syncthreads();               // every thread has read the counts and results of the level before
       for (int i = tid; i < kHistBins; i += NT) hist[i] = 0;
       __syncthreads();
     }
-    if (use_list) {
-      for (uint32_t i = tid; i < ncand; i += NT) {
-        const uint32_t kv = cand[i];
-        if (kv >= lo && kv <= hi) atomicAdd(&hist[(kv - lo) >> shift], 1u);
+    if (cur >= 0) {
+      const uint32_t* cand = list_at(cur);
+      for (uint32_t i = tid; i < nlist; i += NT) {
+        const uint32_t dk = cand[i] - lo;
+        if (dk <= span1) atomicAdd(&hist[dk >> shift], 1u);
       }
-    } else if (level == 0 && full) {
+    } else if (hist_clean && full) {
       // lo and hi are the smallest and largest key of the segment: nothing to test
 #pragma unroll
       for (int e = 0; e < EPT; ++e) atomicAdd(&hist[(key[e] - lo) >> shift], 1u);
@@ -1338,28 +1444,18 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       }
     }
     __syncthreads();
-    if (level == 0) SLKV_STAMP(128 + seg, 3);
+    if (hist_clean) SLKV_STAMP(128 + seg, 3);
     select_bin<NT>(hist, k, sh_scan, res);
-    if (level == 0) SLKV_STAMP(128 + seg, 4);
-    const uint32_t bsel = res[0], cnt_sel = hist[bsel];
+    if (hist_clean) SLKV_STAMP(128 + seg, 4);
+    const uint32_t bsel = res[0];
+    cnt_sel = hist[bsel];
     k = res[1];
+    hist_clean = false;
+    unsynced = true;
     lo = lo + (bsel << shift);
     hi = min(hi, lo + ((1u << shift) - 1u));
     if (shift == 0) break;
-    if (level == 0 && cnt_sel <= kCandCap) {
-      // collect the scores of the chosen digit (their order does not matter for counting); the
-      // results above are not written again before the barrier below
-      const uint32_t span2 = hi - lo;
-#pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (key[e] - lo <= span2) {
-          const uint32_t slot = atomicAdd(&res[2], 1u);
-          if (slot < kCandCap) cand[slot] = key[e];
-        }
-      __syncthreads();
-      ncand = res[2];
-      use_list = true;
-    }
+    pending = true;
   }
   const uint32_t tau = lo, need_eq = k;
   SLKV_STAMP(128 + seg, 5);
