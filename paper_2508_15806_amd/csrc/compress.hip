@@ -1167,12 +1167,16 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   float* P = pooled + tab.score_off[seg];
   const int radius = RADIUS >= 0 ? RADIUS : pool_kernel / 2;
   const bool is_max = pool_mode != SLKV_POOL_AVG;
-  const float fill = is_max ? -INFINITY : 0.f;
+  const float fill = 0.f;                          // scores are >= 0, so zero padding leaves window maxima as they are
   const float inv_p = 1.f / (float)pool_kernel;
 
-  float p[EPT];                                    // pooled scores of this thread in the current round
+  // Keys: bit patterns of the pooled scores (>= 0, so monotone as unsigned integers); positions
+  // past the end of the history get a key above every score.
+  uint32_t key[EPT];
+  const int j0 = EPT * tid;
 
-  // pooled scores from the importance array
+  // keys of the pooled scores from the importance array.  Window maxima are taken on the keys
+  // themselves (integer maxima, three operands at a time); averages in floating point.
   auto pool_all = [&]() {
     const int base = 0;
     // all loads first (clamped addresses, so none depends on a branch), then the LDS writes
@@ -1194,27 +1198,27 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     __syncthreads();
     if (RADIUS >= 0) {
       constexpr int RR = RADIUS >= 0 ? RADIUS : 0;
-      float v[EPT + 2 * RR + 2];
+      float v[EPT + 2 * RR];
 #pragma unroll
       for (int e = 0; e < EPT + 2 * RR; ++e) v[e] = stage[pad_idx<EPT>(EPT * tid + e)];
-      v[EPT + 2 * RR] = v[EPT + 2 * RR + 1] = fill;
       if (is_max) {
-        // window maxima by doubling: widths 2 and 4, then two overlapping pieces cover 2*RR+1
-        float w2[EPT + 2 * RR + 1], w4[EPT + 2 * RR];
+        uint32_t kv[EPT + 2 * RR], t3[EPT + 3];
 #pragma unroll
-        for (int e = 0; e < EPT + 2 * RR + 1; ++e) w2[e] = fmaxf(v[e], v[e + 1]);
+        for (int e = 0; e < EPT + 2 * RR; ++e) kv[e] = score_key(v[e]);
+        if (RR >= 2) {
 #pragma unroll
-        for (int e = 0; e < EPT + 2 * RR - 1; ++e) w4[e] = fmaxf(w2[e], w2[e + 2]);
+          for (int e = 0; e < EPT + RR; ++e) t3[e] = max(max(kv[e], kv[e + 1]), kv[e + 2]);   // RR == 2 reads t3 up to EPT + 1, RR == 3 up to EPT + 2
+        }
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
-          p[e] = RR == 0 ? v[e] : RR == 1 ? fmaxf(w2[e], v[e + 2]) : RR == 2 ? fmaxf(w4[e], v[e + 4]) : fmaxf(w4[e], w4[e + 3]);
+          key[e] = RR == 0 ? kv[e] : RR == 1 ? max(max(kv[e], kv[e + 1]), kv[e + 2]) : RR == 2 ? max(t3[e], t3[e + 2]) : max(max(t3[e], t3[e + 3]), kv[e + 6]);
       } else {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
           float a = v[e];
 #pragma unroll
           for (int t = 1; t <= 2 * RR; ++t) a += v[e + t];
-          p[e] = a * inv_p;
+          key[e] = score_key(a * inv_p);
         }
       }
     } else {
@@ -1225,39 +1229,38 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
           const float x = stage[pad_idx<EPT>(EPT * tid + e + t)];
           a = is_max ? fmaxf(a, x) : a + x;
         }
-        p[e] = is_max ? a : a * inv_p;
+        key[e] = score_key(is_max ? a : a * inv_p);
       }
     }
     __syncthreads();
   };
-  // Keys: bit patterns of the pooled scores (>= 0, so monotone); positions past the end of the
-  // history get a key above every score.
-  uint32_t key[EPT];
-  const int j0 = EPT * tid;
 
-  // pass 1: pooled scores, their range, and (if asked or needed later) the pooled array
+  // pass 1: keys of the pooled scores, the largest key of this thread's own positions, their range
+  // over the segment, and (if asked) the pooled array
   uint32_t kmin = 0xffffffffu, kmax = 0u;
   pool_all();
   SLKV_STAMP(128 + seg, 1);
   if (j0 + EPT <= m) {                             // every thread but the last ones with positions
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      key[e] = score_key(p[e]);
       kmin = min(kmin, key[e]);
       kmax = max(kmax, key[e]);
     }
   } else {
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      key[e] = j0 + e < m ? score_key(p[e]) : kKeyNone;
-      kmin = min(kmin, key[e]);
-      if (key[e] != kKeyNone) kmax = max(kmax, key[e]);
+      if (j0 + e < m) {
+        kmin = min(kmin, key[e]);
+        kmax = max(kmax, key[e]);
+      } else {
+        key[e] = kKeyNone;
+      }
     }
   }
   if (write_pooled) {
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
-      if (j0 + e < m) P[j0 + e] = p[e];
+      if (j0 + e < m) P[j0 + e] = __uint_as_float(key[e]);
   }
   const uint32_t tmax = kmax;                      // largest key of this thread's own positions
   kmin = wave_reduce_to_last(kmin, [](uint32_t a, uint32_t b) { return min(a, b); });
