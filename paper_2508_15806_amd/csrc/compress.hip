@@ -1154,6 +1154,15 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   if (small_seg)
     for (int i = tid; i < kInlineGatherRows; i += NT) sh_pos[i] = 0;
   __syncthreads();
+  // The observation window is kept whatever the scores say: where this kernel also copies the rows
+  // (small segments) and the window is one 16-byte piece per thread at most, the pieces are
+  // fetched right behind the scores and stored at the end, off the critical path.
+  const int lpr = ga.lanes_per_row;
+  const bool win_early = small_seg && w * lpr <= NT;
+  const bool win_mine = win_early && tid < w * lpr;
+  const int win_piece = min(tid, max(w * lpr - 1, 0));           // (threads past the window's pieces fetch its last one again: a load
+  const int win_row = win_piece / lpr, win_c = win_piece % lpr;  //  under a condition would have to be waited for where the branches meet)
+  u32x4 win_k, win_v;
   const bool ranked = kk > 0 && kk < m;
   if (!ranked) {
     if (kk < 0) {
@@ -1196,6 +1205,12 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       stage[pad_idx<EPT>(s)] = (j >= 0 && j < m) ? ld[EPT] : fill;
     }
     __syncthreads();
+    // (behind the barrier: every score has arrived, and nothing waits for these loads before the end)
+    {
+      const int64_t tok = (int64_t)tab.tok_begin[seg] + m + win_row, h = tab.head[seg];
+      win_k = *reinterpret_cast<const u32x4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + win_c * 16);
+      win_v = *reinterpret_cast<const u32x4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + win_c * 16);
+    }
     if (RADIUS >= 0) {
       constexpr int RR = RADIUS >= 0 ? RADIUS : 0;
       float v[EPT + 2 * RR];
@@ -1501,20 +1516,52 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   }  // ranked
 
   // Small segments copy their K/V rows here (saves the gather launch); larger ones are left
-  // to gather_kernel, which skips the segments handled here.
+  // to gather_kernel, which skips the segments handled here.  Four pieces per thread are in
+  // flight at a time.
   if (kept > 0 && small_seg) {
     __syncthreads();                                // sh_pos is complete
     const int64_t tok0 = tab.tok_begin[seg], h = tab.head[seg], row0 = tab.out_off[seg];
-    const int pieces = kept * ga.lanes_per_row;
-    for (int idx = tid; idx < pieces; idx += NT) {
-      const int row = idx / ga.lanes_per_row, c = idx % ga.lanes_per_row;
-      const int64_t tok = tok0 + sh_pos[row];
-      const uint4 kv = *reinterpret_cast<const uint4*>(ga.k + (h * ga.k_stride_head + tok * ga.k_stride_tok) * ga.elt_bytes + c * 16);
-      const uint4 vv = *reinterpret_cast<const uint4*>(ga.v + (h * ga.v_stride_head + tok * ga.v_stride_tok) * ga.elt_bytes + c * 16);
-      const int64_t o = ((row0 + row) * ga.lanes_per_row + c) * 16;
-      *reinterpret_cast<uint4*>(ga.k_out + o) = kv;
-      *reinterpret_cast<uint4*>(ga.v_out + o) = vv;
-      if (ga.pos_out && c == 0) ga.pos_out[row0 + row] = ga.pos_in[tok];
+    const bool win_done = ranked && win_early;      // the window's pieces are in registers
+    const int pieces = (win_done ? kk : kept) * lpr;
+    const uint32_t magic = 0xffffffffu / (uint32_t)lpr + 1u;   // idx / lpr == umulhi(idx, magic) for idx < 2^16 (lpr > 1)
+    struct Piece {
+      u32x4 kq, vq;
+      int row, c;
+      int64_t tok;
+    };
+    auto fetch = [&](int idx, Piece& q) __attribute__((always_inline)) {
+      q.row = lpr == 1 ? idx : (int)__umulhi((uint32_t)idx, magic);
+      q.c = idx - q.row * lpr;
+      if (idx < pieces) {
+        q.tok = tok0 + sh_pos[q.row];
+        q.kq = *reinterpret_cast<const u32x4*>(ga.k + (h * ga.k_stride_head + q.tok * ga.k_stride_tok) * ga.elt_bytes + q.c * 16);
+        q.vq = *reinterpret_cast<const u32x4*>(ga.v + (h * ga.v_stride_head + q.tok * ga.v_stride_tok) * ga.elt_bytes + q.c * 16);
+      }
+    };
+    auto put = [&](int idx, const Piece& q) __attribute__((always_inline)) {
+      if (idx < pieces) {
+        const int64_t o = ((row0 + q.row) * lpr + q.c) * 16;
+        *reinterpret_cast<u32x4*>(ga.k_out + o) = q.kq;
+        *reinterpret_cast<u32x4*>(ga.v_out + o) = q.vq;
+        if (ga.pos_out && q.c == 0) ga.pos_out[row0 + q.row] = ga.pos_in[q.tok];
+      }
+    };
+    for (int base = tid; base < pieces; base += 4 * NT) {
+      Piece q0, q1, q2, q3;
+      fetch(base, q0);
+      fetch(base + NT, q1);
+      fetch(base + 2 * NT, q2);
+      fetch(base + 3 * NT, q3);
+      put(base, q0);
+      put(base + NT, q1);
+      put(base + 2 * NT, q2);
+      put(base + 3 * NT, q3);
+    }
+    if (win_done && win_mine) {
+      const int64_t o = ((row0 + kk + win_row) * lpr + win_c) * 16;
+      *reinterpret_cast<u32x4*>(ga.k_out + o) = win_k;
+      *reinterpret_cast<u32x4*>(ga.v_out + o) = win_v;
+      if (ga.pos_out && win_c == 0) ga.pos_out[row0 + kk + win_row] = ga.pos_in[tok0 + m + win_row];
     }
   }
   SLKV_STAMP(128 + seg, 7);
