@@ -1361,6 +1361,9 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     }
     const uint32_t span1 = hi - lo;
     const int shift = shift_of(span1);
+    if (span1 == 0u) {
+      found = true;                                // k keys or more equal the largest one (all scores equal, for one): it is the threshold
+    } else {
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       const uint32_t dk = key[e] - lo;               // (a key below lo wraps to a difference above any span)
@@ -1385,6 +1388,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       found = true;
     } else {
       pending = true;
+    }
     }
   }
   while (!found) {
