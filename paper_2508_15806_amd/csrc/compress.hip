@@ -765,6 +765,7 @@ constexpr int kSelEPTMid = 8, kSelEPTSmall = 2;   // shorter histories: fewer po
 constexpr int kSelRound = kSelThreads * kSelEPT;
 constexpr int kSelHaloMax = kMaxPool / 2;
 constexpr int kSelRankMax = 256;          // lists up to this length are ranked by direct counting
+constexpr int kSelTrackMax = 512;         // up to this many wanted keys the first level also tracks the largest and smallest key of every digit
 constexpr int kSelCandidates = 12288;     // scores of one first-level digit that the LDS list can hold
 constexpr int kDigitShift = 20;           // first-level digit = key >> 20: sign (0), 8 exponent and 3 mantissa bits
 constexpr uint32_t kKeyNone = 0xffffffffu;
@@ -1250,34 +1251,39 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     __syncthreads();
   };
 
-  // pass 1: keys of the pooled scores, the largest key of this thread's own positions, their range
-  // over the segment, and (if asked) the pooled array
+  // pass 1: keys of the pooled scores, the largest key of each group of GS consecutive positions
+  // (NQ groups per thread), the range of the keys over the segment, and (if asked) the pooled array
+  constexpr int NQ = EPT < 4 ? EPT : 4, GS = EPT / NQ;
   uint32_t kmin = 0xffffffffu, kmax = 0u;
+  uint32_t gmax[NQ];
   pool_all();
   SLKV_STAMP(128 + seg, 1);
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) gmax[q] = 0u;
   if (j0 + EPT <= m) {                             // every thread but the last ones with positions
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       kmin = min(kmin, key[e]);
-      kmax = max(kmax, key[e]);
+      gmax[e / GS] = max(gmax[e / GS], key[e]);
     }
   } else {
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       if (j0 + e < m) {
         kmin = min(kmin, key[e]);
-        kmax = max(kmax, key[e]);
+        gmax[e / GS] = max(gmax[e / GS], key[e]);
       } else {
         key[e] = kKeyNone;
       }
     }
   }
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) kmax = max(kmax, gmax[q]);
   if (write_pooled) {
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
       if (j0 + e < m) P[j0 + e] = __uint_as_float(key[e]);
   }
-  const uint32_t tmax = kmax;                      // largest key of this thread's own positions
   kmin = wave_reduce_to_last(kmin, [](uint32_t a, uint32_t b) { return min(a, b); });
   kmax = wave_reduce_to_last(kmax, [](uint32_t a, uint32_t b) { return max(a, b); });
   if (lane == 63) {
@@ -1310,13 +1316,13 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
   // the range [lo, hi] still in question.  After a digit search the keys of the chosen digit are
   // copied to a list in LDS (two areas in turn), the next level histograms that list, and a list of
   // at most kSelRankMax keys is ranked by direct counting.
-  // Where at least k threads hold positions, two shortcuts come first.  The k-th largest of the
-  // threads' own maxima bounds the k-th largest key from below: its digit is found from a histogram
-  // of one key per thread, and the first level over all keys then counts only those from that
-  // digit's lower edge upwards (a few times k, as a rule), in finer digits.  That level also keeps
-  // the largest and smallest key of every digit: if the chosen digit holds one value only (with
-  // max pooling a run of equal scores, as a rule), or its largest key is the one wanted, the
-  // search ends there.
+  // Where at least k groups hold positions, two shortcuts come first.  The k-th largest of the
+  // groups' maxima bounds the k-th largest key from below: its digit is found from a histogram of
+  // one key per group, and the first level over all keys then counts only those from that digit's
+  // lower edge upwards (a few times k, as a rule), in finer digits.  That level also keeps the
+  // largest and smallest key of every digit: if the chosen digit holds one value only (with max
+  // pooling a run of equal scores, as a rule), or its largest key is the one wanted, the search
+  // ends there.
   uint32_t lo = kmin, hi = kmax, k = (uint32_t)kk;
   auto list_at = [&](int i) { return reinterpret_cast<uint32_t*>(stage) + (i ? kResStageFloats : kResAuxWords); };
   auto list_cap = [](int i) { return (uint32_t)(i ? kResCandidates : kSelRound - kResAuxWords); };
@@ -1347,31 +1353,42 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     cur = dst;
     unsynced = false;
   };
-  const uint32_t owners = (uint32_t)((m + EPT - 1) / EPT);   // threads that hold at least one position
-  if (k <= owners) {
+  const uint32_t groups = (uint32_t)((m + GS - 1) / GS);     // groups that hold at least one position
+  if (k <= groups) {
     {
       const int shift = shift_of(hi - lo);
-      if ((uint32_t)tid < owners) atomicAdd(&hist[(tmax - lo) >> shift], 1u);
+#pragma unroll
+      for (int q = 0; q < NQ; ++q)
+        if (j0 + q * GS < m) atomicAdd(&hist[(gmax[q] - lo) >> shift], 1u);
       __syncthreads();
       SLKV_STAMP(128 + seg, 3);
       select_bin<NT>(hist, k, sh_scan, res);
       SLKV_STAMP(128 + seg, 4);
-      lo += res[0] << shift;                       // k threads hold a key >= lo, so the k-th largest key is >= lo
+      lo += res[0] << shift;                       // k groups hold a key >= lo, so the k-th largest key is >= lo
       hist_clean = false;
     }
     const uint32_t span1 = hi - lo;
     const int shift = shift_of(span1);
     if (span1 == 0u) {
-      found = true;                                // k keys or more equal the largest one (all scores equal, for one): it is the threshold
+      found = true;                                // k groups or more hold the largest key (all scores equal, for one): it is the threshold
+    } else {
+    const bool track = k <= (uint32_t)kSelTrackMax;   // (with many keys wanted the two extra atomics per counted key cost more than they save)
+    if (track) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t dk = key[e] - lo;             // (a key below lo wraps to a difference above any span)
+        if (dk <= span1) {
+          const uint32_t d = dk >> shift;
+          atomicAdd(&aux_hist[d], 1u);
+          atomicMax(&aux_max[d], key[e]);
+          atomicMin(&aux_min[d], key[e]);
+        }
+      }
     } else {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      const uint32_t dk = key[e] - lo;               // (a key below lo wraps to a difference above any span)
-      if (dk <= span1) {
-        const uint32_t d = dk >> shift;
-        atomicAdd(&aux_hist[d], 1u);
-        atomicMax(&aux_max[d], key[e]);
-        atomicMin(&aux_min[d], key[e]);
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t dk = key[e] - lo;
+        if (dk <= span1) atomicAdd(&aux_hist[dk >> shift], 1u);
       }
     }
     __syncthreads();
@@ -1383,9 +1400,11 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     unsynced = true;
     lo = lo + (bsel << shift);
     hi = min(hi, lo + ((1u << shift) - 1u));
-    if (shift == 0 || top == bottom || k == 1u) {
+    if (track && (top == bottom || k == 1u)) {
       lo = top;                                    // one value in the digit, or the largest of the digit is wanted
       found = true;
+    } else if (shift == 0) {
+      found = true;                                // the digit is the key
     } else {
       pending = true;
     }
