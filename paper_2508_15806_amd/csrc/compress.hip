@@ -1106,9 +1106,10 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
 // first load and the last store (no second workgroup to wait for, no re-read).  Thread t owns 32
 // consecutive positions (values reach it through an LDS transposition of coalesced loads), so
 // pooling is a sliding window in registers and the ordered compaction is one block scan of
-// packed (greater, equal) counts plus per-thread bit masks.  The first radix level takes its 11-bit
-// digits relative to the segment's own [min, max] of keys, which spreads the LDS histogram over
-// nearly all bins and leaves few scores in the chosen one.
+// packed (greater, equal) counts plus per-thread bit masks.  The radix levels take their 11-bit
+// digits relative to the range of keys still in question, which spreads the LDS histogram over
+// nearly all bins and leaves few scores in the chosen one; where k allows, the range is first cut
+// from below by the k-th largest of per-group maxima (see the search in the kernel).
 constexpr int kResStageFloats = kSelRound + 2 * kSelHaloMax + ((kSelRound + 2 * kSelHaloMax) >> 5) + 8;
 constexpr int kResCandidates = 3072;   // keys that the list behind the staging array can hold
 constexpr int kResAuxWords = 3 * kHistBins;   // second histogram, largest and smallest key per digit: the start of the staging array, once the scores are in registers
