@@ -104,3 +104,32 @@ def test_captured_ragged_call_with_device_table_replays_like_eager():
             torch.cuda.synchronize()
             for a, b in zip(outs(), refs[i]):
                 assert np.array_equal(a, b), (rep, i)
+
+
+def test_calls_on_two_streams_do_not_interfere():
+    # Calls whose buffers are disjoint may overlap on the GPU (streams of the default priority): each
+    # keeps its own workspace, and the library holds no device state that two calls share.
+    import torch
+    Hq, Hkv, d, w = 16, 4, 128, 32
+    lays = [wl.make_layer((303, i), [6000, 2500], Hq, Hkv, d, w, dtype="bf16", bias_frac=0.05) for i in range(4)]
+    buds = [np.array([300, 77, 1000, 40], dtype=np.int32), np.array([64, 500, 33, 200], dtype=np.int32)]
+    calls = [api.LayerCall("bf16", 2, Hq, Hkv, d, w, lay.cu_seqlens, buds[i & 1]) for i, lay in enumerate(lays)]
+    dev = [(api.to_device(lay.qwin, "bf16"), api.to_device(lay.k, "bf16"), api.to_device(lay.v, "bf16")) for lay in lays]
+    refs = []
+    for call, (q, k, v) in zip(calls, dev):
+        call.run(q, k, v)
+        torch.cuda.synchronize()
+        refs.append(outputs(call))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(4):
+        for call in calls:
+            call.kept_idx.fill_(-1)
+            call.k_out.zero_()
+        torch.cuda.synchronize()
+        for i, (call, (q, k, v)) in enumerate(zip(calls, dev)):
+            with torch.cuda.stream(streams[i & 1]):
+                call.run(q, k, v)
+        torch.cuda.synchronize()
+        for i, call in enumerate(calls):
+            for a, b in zip(outputs(call), refs[i]):
+                assert np.array_equal(a, b), (rep, i)
