@@ -765,6 +765,7 @@ constexpr int kSelEPTMid = 8, kSelEPTSmall = 2;   // shorter histories: fewer po
 constexpr int kSelRound = kSelThreads * kSelEPT;
 constexpr int kSelHaloMax = kMaxPool / 2;
 constexpr int kSelRankMax = 256;          // lists up to this length are ranked by direct counting
+constexpr int kSelTieGroups = 512;        // this many group maxima in the bound's digit switch the histograms to the pile-aware step
 constexpr int kSelTrackMax = 512;         // up to this many wanted keys the first level also tracks the largest and smallest key of every digit
 constexpr int kSelCandidates = 12288;     // scores of one first-level digit that the LDS list can hold
 constexpr int kDigitShift = 20;           // first-level digit = key >> 20: sign (0), 8 exponent and 3 mantissa bits
@@ -1354,6 +1355,41 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     cur = dst;
     unsynced = false;
   };
+  // Histogram step for segments with piles of equal keys (thousands of LDS atomics on one address
+  // would serialise): the lanes of the wave whose key equals that of the first counted lane are
+  // added by that lane in one atomic, likewise those equal to the first counted lane left over;
+  // the other counted lanes add themselves.
+  bool ties = false;
+  auto count_pile = [&](bool in, uint32_t kv, uint32_t d, uint32_t* h, bool with_range) __attribute__((always_inline)) {
+    const unsigned long long act = __builtin_amdgcn_ballot_w64(in);
+    if (act) {                                     // (the same for the whole wave, like `rest` below)
+      const int first = __builtin_ctzll(act);
+      const bool same = in && kv == (uint32_t)__builtin_amdgcn_readlane((int)kv, first);
+      const unsigned long long sm = __builtin_amdgcn_ballot_w64(same);
+      bool mine = in;
+      uint32_t add = 1u;
+      if (same) {
+        mine = lane == first;
+        add = (uint32_t)__popcll(sm);
+      }
+      const unsigned long long rest = act & ~sm;
+      if (rest) {
+        const int second = __builtin_ctzll(rest);
+        const bool same2 = in && kv == (uint32_t)__builtin_amdgcn_readlane((int)kv, second);
+        if (same2) {
+          mine = lane == second;
+          add = (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(same2));
+        }
+      }
+      if (mine) {
+        atomicAdd(&h[d], add);
+        if (with_range) {
+          atomicMax(&aux_max[d], kv);
+          atomicMin(&aux_min[d], kv);
+        }
+      }
+    }
+  };
   const uint32_t groups = (uint32_t)((m + GS - 1) / GS);     // groups that hold at least one position
   if (k <= groups) {
     {
@@ -1365,6 +1401,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       SLKV_STAMP(128 + seg, 3);
       select_bin<NT>(hist, k, sh_scan, res);
       SLKV_STAMP(128 + seg, 4);
+      ties = hist[res[0]] >= (uint32_t)kSelTieGroups;   // many groups share one digit: expect piles of equal keys
       lo += res[0] << shift;                       // k groups hold a key >= lo, so the k-th largest key is >= lo
       hist_clean = false;
     }
@@ -1373,8 +1410,14 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
     if (span1 == 0u) {
       found = true;                                // k groups or more hold the largest key (all scores equal, for one): it is the threshold
     } else {
-    const bool track = k <= (uint32_t)kSelTrackMax;   // (with many keys wanted the two extra atomics per counted key cost more than they save)
-    if (track) {
+    const bool track = ties || k <= (uint32_t)kSelTrackMax;   // (with many keys wanted the two extra atomics per counted key cost more than they save)
+    if (ties) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t dk = key[e] - lo;
+        count_pile(dk <= span1, key[e], dk >> shift, aux_hist, true);
+      }
+    } else if (track) {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
         const uint32_t dk = key[e] - lo;             // (a key below lo wraps to a difference above any span)
@@ -1416,7 +1459,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       // the keys of the chosen digit go to the other list (their order does not matter for counting)
       pending = false;
       const int dst = cur == 0 ? 1 : 0;
-      if (cnt_sel <= list_cap(dst)) {
+      if (cnt_sel <= (cur >= 0 ? list_cap(dst) : (uint32_t)kResCandidates)) {   // (from registers every copied key costs an LDS atomic with its latency)
         begin_list();
         const uint32_t span2 = hi - lo;
         if (cur >= 0) {
@@ -1471,6 +1514,12 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
       for (uint32_t i = tid; i < nlist; i += NT) {
         const uint32_t dk = cand[i] - lo;
         if (dk <= span1) atomicAdd(&hist[dk >> shift], 1u);
+      }
+    } else if (ties) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t dk = key[e] - lo;
+        count_pile(dk <= span1, key[e], dk >> shift, hist, false);
       }
     } else if (hist_clean && full) {
       // lo and hi are the smallest and largest key of the segment: nothing to test
