@@ -213,7 +213,8 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
                                                          int64_t k_stride_head, int R, int Rpad, int w, int CH,
                                                          float c_log2, float* __restrict__ part,
                                                          const float* __restrict__ lse, float* __restrict__ imp,
-                                                         float* __restrict__ lse_out, uint32_t* __restrict__ tickets) {
+                                                         float* __restrict__ lse_out, uint32_t* __restrict__ tickets,
+                                                         int grid2d) {
   constexpr int KS = 4 / RB;               // waves along the keys
   constexpr int TK = kTileKeys;
   constexpr int NSUB = TK / 32 / KS;       // 32-key sub-tiles per wave per tile
@@ -234,18 +235,41 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
   const int rb = wv % RB, ks = wv / RB;
   const int l32 = lane & 31, half = lane >> 5;
 
-  const int bid = blockIdx.x;
+  // Which chunk of which segment.  With a two-dimensional grid (grid2d; the host chooses it when the
+  // segments' chunk counts are alike enough) blockIdx.y is the segment and blockIdx.x the chunk, and
+  // workgroups past a segment's last chunk leave at once; otherwise blockIdx.x counts the chunks of
+  // all segments and the segment is searched in the table.  The table is read through the scalar
+  // cache, cold at every launch, so each dependent lookup costs a memory round trip before the
+  // first key can be requested: the entries of segment blockIdx.y are therefore fetched before it
+  // is known which case applies (y is 0 with a one-dimensional grid: a valid entry either way).
+  struct SegEntry {
+    int32_t n, tok_begin, head, qrow_off, chunk0, chunk1;
+  };
+  auto entry_of = [&](int s) {
+    return SegEntry{tab.n[s], tab.tok_begin[s], tab.head[s], tab.qrow_off[s], tab.chunk_begin[s], tab.chunk_begin[s + 1]};
+  };
+  int seg = (int)blockIdx.y;
+  SegEntry se = entry_of(seg);
+  asm volatile("" :: "s"(se.n), "s"(se.tok_begin), "s"(se.head), "s"(se.qrow_off), "s"(se.chunk0), "s"(se.chunk1));   // fetched here, not behind the branch
+  int bid;
+  if (grid2d) {
+    bid = se.chunk0 + (int)blockIdx.x;
+    if (bid >= se.chunk1) return;
+  } else {
+    bid = blockIdx.x;
+    seg = find_segment(tab.chunk_begin, tab.nseg, bid);
+    se = entry_of(seg);
+  }
   if (PASS == 1) SLKV_STAMP(256 + bid, 0);
-  const int seg = find_segment(tab.chunk_begin, tab.nseg, bid);
-  const int chunk = bid - tab.chunk_begin[seg];
-  const int m = tab.n[seg] - w;
+  const int chunk = bid - se.chunk0;
+  const int m = se.n - w;
   const int key_begin = chunk * CH;
   const int key_end = min(m, key_begin + CH);
   // tiles are processed in pairs (one per register slot); a surplus tile is fully masked
   const int ntiles = ((key_end - key_begin + TK - 1) / TK + 1) & ~1;
   // uniform 64-bit base of the segment's keys + 32-bit byte offsets (the host checks the range)
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(kmat_v) +
-      ((int64_t)tab.head[seg] * k_stride_head + (int64_t)tab.tok_begin[seg] * k_stride_tok) * EB;
+      ((int64_t)se.head * k_stride_head + (int64_t)se.tok_begin * k_stride_tok) * EB;
   const uint32_t row_bytes = (uint32_t)k_stride_tok * (uint32_t)EB;
   const uint32_t piece_off = (uint32_t)(tid % CPR) * 16u;
   const int piece_row = tid / CPR;
@@ -301,7 +325,7 @@ __global__ __launch_bounds__(256, (MT <= 2 ? 2 : 1)) void score_bf16_kernel(cons
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       Pack16 p;
-      p.u = *reinterpret_cast<const u32x4*>(q + ((int64_t)tab.qrow_off[seg] + row) * DK + kk * 16 + half * 8);
+      p.u = *reinterpret_cast<const u32x4*>(q + ((int64_t)se.qrow_off + row) * DK + kk * 16 + half * 8);
       qreg[mt][kk] = p.b;
     }
   }
@@ -1825,22 +1849,31 @@ static void ragged_geometry(const slkv_ragged_desc* d, Geometry& g) {
   }
 }
 
+// Grid of a scoring launch: `chunks` workgroups in a row, or (rows > 0) one row of `per_row`
+// workgroups per segment.
+struct ScoreGrid {
+  int chunks, per_row, rows;
+};
+
 template <int DK, int MT, int RB, int KIND, class TAB>
-static void launch_bf16(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
+static void launch_bf16(int pass, ScoreGrid grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                         const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                         uint32_t* tickets) {
+  // segments with like chunk counts: one grid row per segment (see the kernel's first lines)
+  const bool two = grid.rows > 0;
+  const dim3 gr = two ? dim3((unsigned)grid.per_row, (unsigned)grid.rows) : dim3((unsigned)grid.chunks);
   if (pass == 1)
-    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, KIND, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 1, KIND, TAB>), gr, dim3(256), 0, st, tab, (const uint16_t*)q,
                        k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
-                       lse, tickets);
+                       lse, tickets, two ? 1 : 0);
   else
-    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, KIND, TAB>), dim3(grid), dim3(256), 0, st, tab, (const uint16_t*)q,
+    SLKV_LAUNCH((score_bf16_kernel<DK, MT, RB, 2, KIND, TAB>), gr, dim3(256), 0, st, tab, (const uint16_t*)q,
                        k, g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp,
-                       lse, tickets);
+                       lse, tickets, two ? 1 : 0);
 }
 
 template <int DK, int KIND, class TAB>
-static void launch_bf16_rows(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
+static void launch_bf16_rows(int pass, ScoreGrid grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                              const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                              uint32_t* tickets) {
   if (p.R <= 64) launch_bf16<DK, 1, 2, KIND>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
@@ -1850,7 +1883,7 @@ static void launch_bf16_rows(int pass, int grid, hipStream_t st, const TAB& tab,
 }
 
 template <class TAB>
-static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
+static void launch_score(int pass, ScoreGrid grid, hipStream_t st, const TAB& tab, const void* q, const void* k,
                          const Geometry& g, const Plan& p, float c_log2, float* part, float* lse, float* imp,
                          uint32_t* tickets) {
   if (g.dtype == SLKV_BF16) {
@@ -1864,7 +1897,7 @@ static void launch_score(int pass, int grid, hipStream_t st, const TAB& tab, con
     else launch_bf16_rows<64, 2>(pass, grid, st, tab, q, k, g, p, c_log2, part, lse, imp, tickets);
   } else {
 #define SLKV_F32_LAUNCH(DKV, PS)                                                                                     \
-  SLKV_LAUNCH((score_f32_kernel<DKV, PS, TAB>), dim3(grid), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
+  SLKV_LAUNCH((score_f32_kernel<DKV, PS, TAB>), dim3(grid.chunks), dim3(256), 0, st, tab, (const float*)q, (const float*)k, \
                      g.k_stride_tok, g.k_stride_head, p.R, p.Rpad, g.w, p.CH, c_log2, part, lse, imp, lse, tickets)
     if (g.d == 128) { if (pass == 1) SLKV_F32_LAUNCH(128, 1); else SLKV_F32_LAUNCH(128, 2); }
     else { if (pass == 1) SLKV_F32_LAUNCH(64, 1); else SLKV_F32_LAUNCH(64, 2); }
@@ -2062,16 +2095,23 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
   for (const Seg& sg : g.segs)
     if (seg_ranked(sg.n, g.w, sg.cap) && sg.n - g.w > kSelRound) resident_select = false;
   const int nseg = (int)S;
-  auto launch_group = [&](const auto& tab, int chunks, int blocks, bool any_large, int64_t rows) -> slkv_status {
+  auto launch_group = [&](const auto& tab, int chunks, int max_chunks, int blocks, bool any_large, int64_t rows) -> slkv_status {
     using TAB = std::decay_t<decltype(tab)>;
+    // one grid row per segment where that wastes few workgroups (a segment with fewer chunks than
+    // the longest leaves the surplus of its row empty), else one row over all chunks
+    ScoreGrid sgrid{chunks, 0, 0};
+    if (tab.nseg <= 65535 && (int64_t)max_chunks * tab.nseg <= (int64_t)chunks * 2) {
+      sgrid.per_row = max_chunks;
+      sgrid.rows = tab.nseg;
+    }
     if (chunks > 0) {
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_STATS, st);
-        launch_score(1, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp, tickets);
+        launch_score(1, sgrid, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp, tickets);
       }
       {
         ScopedKernelTimer tm(SLKV_K_SCORE_ACCUM, st);
-        launch_score(2, chunks, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp, tickets);
+        launch_score(2, sgrid, st, tab, d_qwin, d_k, g, p, c_log2, part, lse, imp, tickets);
       }
     }
     {
@@ -2115,7 +2155,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
     dev.nseg = (int32_t)S;
   }
   // running totals over the call: output rows, key chunks, selection blocks, block histograms, tickets
-  int64_t out_run = 0, chunks = 0, blocks = 0, hist_run = 0, tick_run = 0;
+  int64_t out_run = 0, chunks = 0, max_chunks = 0, blocks = 0, hist_run = 0, tick_run = 0;
   bool any_large = false;
   for (int64_t s0 = 0; s0 < S; s0 += kMaxSegPerLaunch) {
     SegTable tab;
@@ -2142,6 +2182,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
       tab.hblk[i] = (int32_t)hist_run;
       tab.tick[i] = (int32_t)tick_run;
       chunks += nc;
+      max_chunks = std::max(max_chunks, nc);
       blocks += nb;
       hist_run += nb;
       if (nc > 1) tick_run += 1;
@@ -2155,11 +2196,11 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
     }
     tab.total_chunks = (int32_t)chunks;
     if (dev_table) SLKV_LAUNCH(table_write_kernel, dim3(1), dim3(kMaxSegPerLaunch + 64), 0, st, tab, (int)s0, dev);
-    else return launch_group(tab, (int)chunks, (int)blocks, any_large, out_run);
+    else return launch_group(tab, (int)chunks, (int)max_chunks, (int)blocks, any_large, out_run);
   }
   if (dev_table) {
     dev.total_chunks = (int32_t)chunks;
-    return launch_group(dev, (int)chunks, (int)blocks, any_large, out_run);
+    return launch_group(dev, (int)chunks, (int)max_chunks, (int)blocks, any_large, out_run);
   }
   return SLKV_OK;
 }
