@@ -784,6 +784,7 @@ struct GatherArgs {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelBlock = 4096;           // history positions per phase-A block
+constexpr int kSelEmitThreads = 256;      // workgroup of the block-wise count / emit kernels (16 positions per thread)
 constexpr int kSelEPT = 32;
 constexpr int kSelEPTMid = 8, kSelEPTSmall = 2;   // shorter histories: fewer positions per thread in the one-workgroup kernel
 constexpr int kSelRound = kSelThreads * kSelEPT;
@@ -863,9 +864,9 @@ __global__ __launch_bounds__(kSelThreads) void select_pool_kernel(const TAB tab,
 // Phase B: one workgroup per segment (unranked segments only write their positions).
 template <class TAB>
 __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab, int w, const float* __restrict__ pooled,
-                                                                  const uint32_t* __restrict__ blockhist,
+                                                                  uint32_t* __restrict__ blockhist,
                                                                   int32_t* __restrict__ kept_idx, int64_t* __restrict__ d_out_offsets,
-                                                                  const GatherArgs ga) {
+                                                                  const GatherArgs ga, int split_emit) {
   constexpr int NT = kSelThreads, NW = kSelWaves, EPT = kSelEPT, ROUND = kSelRound;
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t cand[kSelCandidates];
@@ -883,7 +884,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
   const int kk = tab.kkeep[seg];
   const int m = n - w;
   const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
-  const bool small_seg = kept <= kInlineGatherRows;
+  const bool small_seg = !split_emit && kept <= kInlineGatherRows;   // (split: every row is copied by gather_kernel)
   int32_t* out = kept_idx + tab.out_off[seg];
   if (d_out_offsets && tid == 0) {
     d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
@@ -1055,6 +1056,16 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     const uint32_t tau = lo, need_eq = k;
     SLKV_STAMP(bid, 7);
 
+    if (split_emit) {
+      // The kept positions are written by select_count_kernel + select_emit_kernel, one workgroup
+      // per block of the history: they find the threshold in words 2 and 3 of the segment's first
+      // block histogram (read in full above, not needed again in this call).
+      if (tid == 0) {
+        uint32_t* row0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+        row0[2] = tau;
+        row0[3] = need_eq;
+      }
+    } else {
     // ---------------- ordered compaction: slot = (#greater before) + min(#equal before, need_eq)
     uint32_t carry_g = 0, carry_e = 0;
     for (int r = 0; r < rounds; ++r) {
@@ -1102,6 +1113,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
       carry_e += tot_e;
       __syncthreads();
     }
+    }
     for (int j = tid; j < w; j += NT) emit(kk + j, m + j);
     SLKV_STAMP(bid, 8);
   }
@@ -1124,6 +1136,140 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     }
   }
   SLKV_STAMP(bid, 9);
+}
+
+// Ordered compaction of long histories, spread over the blocks of select_pool_kernel (one
+// workgroup per kSelBlock positions) once select_rank_kernel has left the threshold tau and the
+// number need_eq of positions equal to tau that are kept (the first ones in position order):
+//   select_count_kernel: positions of the block above tau / equal to tau -> words 0, 1 of the
+//     block's histogram row (free by now);
+//   select_emit_kernel: sums the counts of the segment's earlier blocks, scans its own positions
+//     (a wave owns 1024 consecutive ones) and writes the kept ones to their output slots:
+//     slot = (#greater before) + min(#equal before, need_eq).
+template <class TAB>
+__global__ __launch_bounds__(kSelEmitThreads) void select_count_kernel(const TAB tab, int w, const float* __restrict__ pooled,
+                                                                   uint32_t* __restrict__ blockhist, int seg0) {
+  constexpr int NT = kSelEmitThreads, PER = kSelBlock / NT;
+  __shared__ uint32_t sh[NT / 64];
+  const int tid = threadIdx.x;
+  // seg0 >= 0: one grid row per segment (no search in the table; blocks past the segment's last
+  // one leave at once); seg0 < 0: one row over all blocks
+  int seg, blk;
+  if (seg0 >= 0) {
+    seg = seg0 + (int)blockIdx.y;
+    blk = blockIdx.x;
+    if (blk >= tab.blk_begin[seg + 1] - tab.blk_begin[seg]) return;
+  } else {
+    seg = find_segment(tab.blk_begin, tab.nseg, (int)blockIdx.x);
+    blk = (int)blockIdx.x - tab.blk_begin[seg];
+  }
+  const int m = tab.n[seg] - w;
+  const int kk = tab.kkeep[seg];
+  if (!(kk > 0 && kk < m)) return;                    // (such segments have no block)
+  uint32_t* row0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+  const uint32_t tau = row0[2];
+  const float* P = pooled + tab.score_off[seg];
+  const int p0 = blk * kSelBlock + tid;               // (which thread counts which position does not matter here)
+  uint32_t cg = 0, ce = 0;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int j = p0 + e * NT;
+    const uint32_t kv = score_key(P[min(j, m - 1)]);
+    if (j < m) {
+      cg += kv > tau ? 1u : 0u;
+      ce += kv == tau ? 1u : 0u;
+    }
+  }
+  const uint32_t tot = block_sum<NT, uint32_t>((ce << 16) | cg, sh);   // a block holds 4096 positions: 13 bits each
+  if (tid == 0) {
+    uint32_t* row = row0 + (size_t)blk * kHistBins;
+    row[0] = tot & 0xffffu;
+    row[1] = tot >> 16;
+  }
+}
+
+template <class TAB>
+__global__ __launch_bounds__(kSelEmitThreads) void select_emit_kernel(const TAB tab, int w, const float* __restrict__ pooled,
+                                                                  const uint32_t* __restrict__ blockhist,
+                                                                  int32_t* __restrict__ kept_idx, int seg0) {
+  constexpr int NT = kSelEmitThreads, PER = kSelBlock / NT;
+  __shared__ uint32_t sh[NT / 64];
+  const int tid = threadIdx.x;
+  // seg0 >= 0: one grid row per segment (no search in the table; blocks past the segment's last
+  // one leave at once); seg0 < 0: one row over all blocks
+  int seg, blk;
+  if (seg0 >= 0) {
+    seg = seg0 + (int)blockIdx.y;
+    blk = blockIdx.x;
+    if (blk >= tab.blk_begin[seg + 1] - tab.blk_begin[seg]) return;
+  } else {
+    seg = find_segment(tab.blk_begin, tab.nseg, (int)blockIdx.x);
+    blk = (int)blockIdx.x - tab.blk_begin[seg];
+  }
+  const int m = tab.n[seg] - w;
+  const int kk = tab.kkeep[seg];
+  if (!(kk > 0 && kk < m)) return;
+  const uint32_t* row0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+  const uint32_t tau = row0[2], need_eq = row0[3];
+  const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
+  int32_t* out = kept_idx + tab.out_off[seg];
+  const float* P = pooled + tab.score_off[seg];
+  // this block's own positions first (the loads fly while the earlier blocks are added up): a wave
+  // owns 64 * PER consecutive positions, lane l the positions 64 j + l, so that loads are coalesced
+  // and ballots are in position order
+  const int lane = tid & 63, wv = tid >> 6;
+  const int p0 = blk * kSelBlock + wv * (64 * PER) + lane;
+  float pv[PER];
+#pragma unroll
+  for (int j = 0; j < PER; ++j) pv[j] = P[min(p0 + j * 64, m - 1)];
+  // kept positions before this block: greater, and equal (capped at need_eq when they are used)
+  uint32_t pg = 0, pe = 0;
+  for (int b = tid; b < blk; b += NT) {
+    pg += row0[(size_t)b * kHistBins];
+    pe += row0[(size_t)b * kHistBins + 1];
+  }
+  // (a segment has at most 2^31 / kSelBlock blocks of at most 4096 positions: the sums fit 32 bits each)
+  const uint32_t g0 = block_sum<NT, uint32_t>(pg, sh);
+  const uint32_t e0 = block_sum<NT, uint32_t>(pe, sh);
+  uint32_t key[PER];
+  uint32_t wg = 0, we = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    key[j] = p0 + j * 64 < m ? score_key(pv[j]) : kKeyNone;
+    wg += (uint32_t)__popcll(__ballot(key[j] > tau && key[j] != kKeyNone));
+    we += (uint32_t)__popcll(__ballot(key[j] == tau));
+  }
+  __shared__ uint32_t sh_wg[NT / 64], sh_we[NT / 64];
+  if (lane == 0) {
+    sh_wg[wv] = wg;
+    sh_we[wv] = we;
+  }
+  __syncthreads();
+  uint32_t g = g0, q = e0;                            // greater / equal before this wave's positions
+#pragma unroll
+  for (int v2 = 0; v2 < NT / 64; ++v2)
+    if (v2 < wv) {
+      g += sh_wg[v2];
+      q += sh_we[v2];
+    }
+  if (wg + we) {
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const bool isg = key[j] > tau && key[j] != kKeyNone;
+      const bool ise = key[j] == tau;
+      const unsigned long long mg = __ballot(isg), me = __ballot(ise);
+      if (mg | me) {
+        const uint32_t my_g = g + lanes_below(mg);
+        const uint32_t my_e = q + lanes_below(me);    // ties are taken in position order
+        uint32_t pos = 0xffffffffu;
+        if (isg) pos = my_g + min(my_e, need_eq);
+        else if (ise && my_e < need_eq) pos = my_g + my_e;
+        if (pos < (uint32_t)kept) out[pos] = p0 + j * 64;
+        g += (uint32_t)__popcll(mg);
+        q += (uint32_t)__popcll(me);
+      }
+    }
+  }
 }
 
 // The same selection for launches whose histories all fit one round of kSelRound positions: one
@@ -1667,7 +1813,7 @@ __global__ __launch_bounds__(kSelThreads) void select_resident_kernel(const TAB 
 // Copies kept rows of K and V (bit copies) into the packed output; one 16-byte lane per piece.
 template <class TAB>
 __global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const GatherArgs ga,
-                                                     const int32_t* __restrict__ kept_idx) {
+                                                     const int32_t* __restrict__ kept_idx, int all_segments) {
   const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t rel = g / ga.lanes_per_row;
   const int c = (int)(g % ga.lanes_per_row);
@@ -1675,7 +1821,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const TAB tab, const Gather
   const int64_t row = row0 + rel;
   if (row >= row1) return;
   const int seg = find_segment(tab.out_off, tab.nseg, (int)row);
-  if (tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by the selection kernel
+  if (!all_segments && tab.out_off[seg + 1] - tab.out_off[seg] <= kInlineGatherRows) return;   // done by the selection kernel
   // (a position outside the segment cannot come out of the selection; clamped all the same, so
   // that no input can turn into an out-of-bounds read here)
   const int64_t tok = (int64_t)tab.tok_begin[seg] + min(max(kept_idx[row], 0), max(tab.n[seg] - 1, 0));
@@ -1924,8 +2070,23 @@ static void launch_select(int nseg, int blocks, hipStream_t st, const TAB& tab, 
     }
   }
 #undef SLKV_POOL_LAUNCH
+  // with blocks, the ordered compaction runs per block (two short launches over the whole chip)
+  // instead of per segment inside the ranking workgroup
+  const int split = blocks > 0 ? 1 : 0;
   SLKV_LAUNCH(select_rank_kernel<TAB>, dim3(nseg), dim3(kSelThreads), 0, st, tab, g.w, (const float*)pooled,
-              (const uint32_t*)blockhist, kept_idx, d_out_offsets, ga);
+              blockhist, kept_idx, d_out_offsets, ga, split);
+  if (split) {
+    int64_t longest = 0;
+    for (const Seg& sg : g.segs) longest = std::max<int64_t>(longest, seg_blocks(sg, g.w));
+    // a grid row per segment unless that would launch mostly empty workgroups (one long history
+    // among many short ones) or more rows than a grid has
+    const bool rows = nseg <= 65535 && longest * nseg <= 4 * (int64_t)blocks;
+    const dim3 grid = rows ? dim3((unsigned)longest, (unsigned)nseg) : dim3((unsigned)blocks);
+    SLKV_LAUNCH(select_count_kernel<TAB>, grid, dim3(kSelEmitThreads), 0, st, tab, g.w, (const float*)pooled, blockhist,
+                rows ? 0 : -1);
+    SLKV_LAUNCH(select_emit_kernel<TAB>, grid, dim3(kSelEmitThreads), 0, st, tab, g.w, (const float*)pooled,
+                (const uint32_t*)blockhist, kept_idx, rows ? 0 : -1);
+  }
 }
 
 // select_resident_kernel needs more LDS than a kernel gets by default: the limit is raised for all
@@ -2125,10 +2286,12 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
         launch_select(nseg, blocks, st, tab, g, imp, pooled, blockhist, d_kept_idx, d_out_offsets, ga);
       }
     }
-    if (any_large) {
+    const bool gather_all = !resident_select && blocks > 0;   // the block-wise selection copies no rows itself
+    if ((any_large || gather_all) && rows > 0) {
       ScopedKernelTimer tm(SLKV_K_GATHER, st);
       const int64_t threads = rows * lanes_per_row;
-      SLKV_LAUNCH(gather_kernel<TAB>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx);
+      SLKV_LAUNCH(gather_kernel<TAB>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tab, ga, d_kept_idx,
+                  gather_all ? 1 : 0);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SLKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));

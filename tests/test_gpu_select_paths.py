@@ -73,3 +73,12 @@ def test_paths_agree_bit_for_bit():
             os.environ["SLKV_SELECT"] = old
     for key in ("offsets", "kept", "k_out", "v_out", "pooled"):
         assert np.array_equal(outs["resident"][key], outs["blocks"][key]), key
+
+
+def test_one_long_history_among_many_short_ones(select_path):
+    # block-wise compaction with one grid row over all blocks (a grid row per segment would be mostly
+    # empty here), segments that are not ranked in between, more than 64 segments (device table)
+    lens = [45000] + [150 + 37 * (i % 9) for i in range(70)] + [20]
+    lay = wl.make_layer((604,), lens, 2, 1, 64, 16, dtype="bf16", bias_frac=0.03)
+    gpu, rep = run(lay, np.array([180], dtype=np.int32))
+    assert rep["segments"] == len(lens) and rep["ranked"] >= 40 and rep["tolerant"] == 0
