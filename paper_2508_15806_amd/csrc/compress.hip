@@ -753,21 +753,23 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
 // Pooling + top-k (Algorithm 3, steps 7-8).  Writes the kept positions: history positions
 // ascending, then the window.
 //
-// Histories longer than one round of kSelRound positions take two kernels:
+// Histories longer than one round of kSelRound positions take four kernels (the last two are
+// described where they are defined):
 //   select_pool_kernel: the history is cut into blocks of kSelBlock positions, one workgroup each:
 //     pool the block's importance scores (halo from the neighbours), write the pooled scores,
 //     histogram their leading 11 key bits, write the block's histogram;
 //   select_rank_kernel: one workgroup per segment adds the block histograms, picks the digit that
 //     holds the k-th largest score, collects that digit's scores in LDS and narrows them down to
 //     the exact k-th largest value tau and the number of scores equal to tau that belong to the
-//     top k (ties go to lower positions); then one ordered compaction of the positions with
-//     score > tau, or == tau among the first `need_eq`.
+//     top k (ties go to lower positions), and leaves both for select_count_kernel and
+//     select_emit_kernel, which write the kept history positions block by block: those with
+//     score > tau, or == tau among the first `need_eq`.  The window's positions, and the
+//     positions of segments that are not ranked, are written here.
 // (One kernel with a per-segment ticket, the last block doing the ranking, was measured and
 // dropped: with 1024-thread workgroups at one per CU, the blocks of later segments queue behind
 // ranking workgroups and start tens of microseconds late.)
 // Keys are the bit patterns of the pooled scores (>= 0, so monotone).  While ranking, a wave owns
-// 2048 consecutive positions of a round, lane l the positions 64*j + l (j < 32): ballots are in
-// position order, so the ordered compaction needs no scan beyond the 16 wave totals.
+// 2048 consecutive positions of a round, lane l the positions 64*j + l (j < 32).
 constexpr int kInlineGatherRows = 256;    // segments up to this many kept rows are gathered by the selection kernel
 
 struct GatherArgs {
@@ -884,7 +886,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
   const int kk = tab.kkeep[seg];
   const int m = n - w;
   const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
-  const bool small_seg = !split_emit && kept <= kInlineGatherRows;   // (split: every row is copied by gather_kernel)
+  const bool small_seg = !split_emit && kept <= kInlineGatherRows;   // (split_emit: the launch has ranked segments, and gather_kernel copies every row)
   int32_t* out = kept_idx + tab.out_off[seg];
   if (d_out_offsets && tid == 0) {
     d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
@@ -1056,63 +1058,13 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     const uint32_t tau = lo, need_eq = k;
     SLKV_STAMP(bid, 7);
 
-    if (split_emit) {
-      // The kept positions are written by select_count_kernel + select_emit_kernel, one workgroup
-      // per block of the history: they find the threshold in words 2 and 3 of the segment's first
-      // block histogram (read in full above, not needed again in this call).
-      if (tid == 0) {
-        uint32_t* row0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
-        row0[2] = tau;
-        row0[3] = need_eq;
-      }
-    } else {
-    // ---------------- ordered compaction: slot = (#greater before) + min(#equal before, need_eq)
-    uint32_t carry_g = 0, carry_e = 0;
-    for (int r = 0; r < rounds; ++r) {
-      if (multi) load_round(r);
-      uint32_t wg = 0, we = 0;
-#pragma unroll
-      for (int j = 0; j < EPT; ++j) {
-        wg += (uint32_t)__popcll(__ballot(key[j] > tau && key[j] != kKeyNone));
-        we += (uint32_t)__popcll(__ballot(key[j] == tau));
-      }
-      if (lane == 0) {
-        sh_wg[wv] = wg;
-        sh_we[wv] = we;
-      }
-      __syncthreads();
-      uint32_t g_before = carry_g, e_before = carry_e, tot_g = 0, tot_e = 0;
-#pragma unroll
-      for (int v2 = 0; v2 < NW; ++v2) {
-        const uint32_t a = sh_wg[v2], b = sh_we[v2];
-        if (v2 < wv) {
-          g_before += a;
-          e_before += b;
-        }
-        tot_g += a;
-        tot_e += b;
-      }
-      if (wg + we) {
-        const int base = r * ROUND + wv * (64 * EPT) + lane;
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-          const bool g = key[j] > tau && key[j] != kKeyNone;
-          const bool e = key[j] == tau;
-          const unsigned long long mg = __ballot(g), me = __ballot(e);
-          if (mg | me) {
-            const uint32_t my_g = g_before + lanes_below(mg);
-            const uint32_t my_e = e_before + lanes_below(me);   // ties are taken in position order
-            if (g) emit((int)(my_g + min(my_e, need_eq)), base + j * 64);
-            else if (e && my_e < need_eq) emit((int)(my_g + my_e), base + j * 64);
-            g_before += (uint32_t)__popcll(mg);
-            e_before += (uint32_t)__popcll(me);
-          }
-        }
-      }
-      carry_g += tot_g;
-      carry_e += tot_e;
-      __syncthreads();
-    }
+    // The kept history positions are written by select_count_kernel + select_emit_kernel, one
+    // workgroup per block of the history: they find the threshold in words 2 and 3 of the segment's
+    // first block histogram (read in full above, not needed again in this call).
+    if (tid == 0) {
+      uint32_t* row0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+      row0[2] = tau;
+      row0[3] = need_eq;
     }
     for (int j = tid; j < w; j += NT) emit(kk + j, m + j);
     SLKV_STAMP(bid, 8);
