@@ -868,7 +868,8 @@ template <class TAB>
 __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab, int w, const float* __restrict__ pooled,
                                                                   uint32_t* __restrict__ blockhist,
                                                                   int32_t* __restrict__ kept_idx, int64_t* __restrict__ d_out_offsets,
-                                                                  const GatherArgs ga, int split_emit) {
+                                                                  const GatherArgs ga, int split_emit,
+                                                                  const uint32_t* __restrict__ lists, int phase) {
   constexpr int NT = kSelThreads, NW = kSelWaves, EPT = kSelEPT, ROUND = kSelRound;
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t cand[kSelCandidates];
@@ -888,7 +889,7 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
   const int kept = tab.out_off[seg + 1] - tab.out_off[seg];
   const bool small_seg = !split_emit && kept <= kInlineGatherRows;   // (split_emit: the launch has ranked segments, and gather_kernel copies every row)
   int32_t* out = kept_idx + tab.out_off[seg];
-  if (d_out_offsets && tid == 0) {
+  if (d_out_offsets && tid == 0 && phase != 0) {
     d_out_offsets[tab.seg_global[seg]] = tab.out_off[seg];
     if (seg == tab.nseg - 1) d_out_offsets[tab.seg_global[seg] + 1] = tab.out_off[tab.nseg];
   }
@@ -903,6 +904,14 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     for (int i = tid; i < kInlineGatherRows; i += NT) sh_pos[i] = 0;
   __syncthreads();
   const bool ranked = kk > 0 && kk < m;
+  // Ranked segments take two launches of this kernel with select_collect_kernel between them
+  // (words 4.. of the segment's first histogram row carry the state across):
+  //   phase 0: add up the block histograms, find the first-level digit of the k-th largest score;
+  //   (collect: the blocks copy their scores of that digit to the segment's list in memory)
+  //   phase 1: rank the list, or, if the digit holds more scores than the LDS list, narrow it by
+  //            sweeps over the pooled array; write the window's positions.
+  if (phase == 0 && !ranked) return;
+  uint32_t* const hdr = blockhist + (size_t)tab.hblk[seg] * kHistBins;   // (used for ranked segments only)
   if (!ranked) {
     if (kk < 0) {
       for (int j = tid; j < n; j += NT) emit(j, j);
@@ -911,21 +920,21 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     }
   } else {
     const float* P = pooled + tab.score_off[seg];
-    {
+    if (phase == 0) {
       // first-level histogram of the segment: the sum of its blocks' histograms
       static_assert(kHistBins == 2 * NT, "a thread adds up two bins");
       const uint32_t* bh0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
       uint32_t a0 = 0, a1 = 0;
-      for (int b0 = 0; b0 < nblk; b0 += 8) {              // 16 loads in flight
-        uint32_t v0[8], v1[8];
+      for (int b0 = 0; b0 < nblk; b0 += 24) {             // 48 loads in flight
+        uint32_t v0[24], v1[24];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 24; ++u) {
           const int b = min(b0 + u, nblk - 1);
           v0[u] = bh0[(size_t)b * kHistBins + tid];
           v1[u] = bh0[(size_t)b * kHistBins + NT + tid];
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 24; ++u)
           if (b0 + u < nblk) {
             a0 += v0[u];
             a1 += v1[u];
@@ -934,9 +943,21 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
       hist[tid] = a0;
       hist[NT + tid] = a1;
       __syncthreads();
+      SLKV_STAMP(bid, 3);
+      select_bin<NT>(hist, (uint32_t)kk, sh_scan, res);
+      if (tid == 0) {
+        const uint32_t in_range = hist[res[0]];
+        hdr[4] = res[0] << kDigitShift;                    // [lo, hi]: the keys of the chosen digit
+        hdr[5] = (res[0] << kDigitShift) + ((1u << kDigitShift) - 1u);
+        hdr[6] = res[1];                                  // rank of the wanted key inside the digit
+        hdr[7] = 0;                                       // length of the list (filled by the blocks)
+        hdr[8] = in_range;
+        hdr[9] = in_range <= (uint32_t)kSelCandidates ? 1u : 0u;   // 1: the blocks list the digit's scores
+      }
+      SLKV_STAMP(bid, 5);
+      return;
     }
-    SLKV_STAMP(bid, 3);
-    // ---------------- phase B: the k-th largest pooled score of the segment
+    // ---------------- the k-th largest pooled score of the segment
     const int rounds = (m + ROUND - 1) / ROUND;
     const bool multi = rounds > 1;
     uint32_t key[EPT];
@@ -956,45 +977,18 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
         for (int j = 0; j < EPT; ++j) f(key[j]);
       }
     };
-    if (!multi) load_round(0);
-    SLKV_STAMP(bid, 4);
-
-    uint32_t k = (uint32_t)kk;
-    select_bin<NT>(hist, k, sh_scan, res);
-    SLKV_STAMP(bid, 5);
-    uint32_t in_range = hist[res[0]];
-    uint32_t lo = res[0] << kDigitShift;
-    uint32_t hi = lo + ((1u << kDigitShift) - 1u);
-    k = res[1];
-    __syncthreads();
-
-    // the scores of the chosen digit, as an unordered list in LDS (if they fit)
-    const bool use_list = in_range <= (uint32_t)kSelCandidates;
-    const uint32_t ncand = in_range;
+    uint32_t lo = hdr[4], hi = hdr[5], k = hdr[6], in_range = hdr[8];
+    const bool use_list = hdr[9] != 0u;
+    const uint32_t ncand = min(hdr[7], (uint32_t)kSelCandidates);   // (== in_range when the list is used)
     if (use_list) {
-      if (tid == 0) res[2] = 0;
+      // the scores of the chosen digit, listed by the blocks: into LDS
+      const uint32_t* L = lists + tab.score_off[seg];
+      for (uint32_t i = tid; i < ncand; i += NT) cand[i] = L[i];
       __syncthreads();
-      for (int r = 0; r < rounds; ++r) {
-        if (multi) load_round(r);
-        uint32_t c = 0;
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) c += (uint32_t)__popcll(__ballot(key[j] >= lo && key[j] <= hi));
-        uint32_t base = 0;
-        if (c) {
-          if (lane == 0) base = atomicAdd(&res[2], c);
-          base = (uint32_t)__shfl((int)base, 0, 64);
-#pragma unroll
-          for (int j = 0; j < EPT; ++j) {
-            const bool in = key[j] >= lo && key[j] <= hi;
-            const unsigned long long mask = __ballot(in);
-            const uint32_t slot = base + lanes_below(mask);
-            if (in && slot < (uint32_t)kSelCandidates) cand[slot] = key[j];
-            base += (uint32_t)__popcll(mask);
-          }
-        }
-      }
-      __syncthreads();
+    } else if (!multi) {
+      load_round(0);
     }
+    SLKV_STAMP(bid, 4);
     SLKV_STAMP(bid, 6);
     // narrow [lo, hi] down to one value: 11 bits per level over what is left of the range
     for (;;) {
@@ -1062,9 +1056,8 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     // workgroup per block of the history: they find the threshold in words 2 and 3 of the segment's
     // first block histogram (read in full above, not needed again in this call).
     if (tid == 0) {
-      uint32_t* row0 = blockhist + (size_t)tab.hblk[seg] * kHistBins;
-      row0[2] = tau;
-      row0[3] = need_eq;
+      hdr[2] = tau;
+      hdr[3] = need_eq;
     }
     for (int j = tid; j < w; j += NT) emit(kk + j, m + j);
     SLKV_STAMP(bid, 8);
@@ -1088,6 +1081,58 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
     }
   }
   SLKV_STAMP(bid, 9);
+}
+
+// Between the two phases of select_rank_kernel: every block copies its scores of the digit chosen
+// for its segment (keys in [lo, hi], words 4 and 5 of the segment's first histogram row) to the
+// segment's list in memory, in any order: one atomic on the list's length (word 7) per wave.
+// Nothing is listed when the digit holds more scores than the ranking workgroup's LDS list (word 9).
+template <class TAB>
+__global__ __launch_bounds__(kSelEmitThreads) void select_collect_kernel(const TAB tab, int w, const float* __restrict__ pooled,
+                                                                     uint32_t* __restrict__ blockhist,
+                                                                     uint32_t* __restrict__ lists, int seg0) {
+  constexpr int NT = kSelEmitThreads, PER = kSelBlock / NT;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int seg, blk;
+  if (seg0 >= 0) {
+    seg = seg0 + (int)blockIdx.y;
+    blk = blockIdx.x;
+    if (blk >= tab.blk_begin[seg + 1] - tab.blk_begin[seg]) return;
+  } else {
+    seg = find_segment(tab.blk_begin, tab.nseg, (int)blockIdx.x);
+    blk = (int)blockIdx.x - tab.blk_begin[seg];
+  }
+  const int m = tab.n[seg] - w;
+  const int kk = tab.kkeep[seg];
+  if (!(kk > 0 && kk < m)) return;
+  uint32_t* hdr = blockhist + (size_t)tab.hblk[seg] * kHistBins;
+  const float* P = pooled + tab.score_off[seg];
+  const int p0 = blk * kSelBlock + wv * (64 * PER) + lane;
+  float pv[PER];
+#pragma unroll
+  for (int j = 0; j < PER; ++j) pv[j] = P[min(p0 + j * 64, m - 1)];
+  if (hdr[9] == 0u) return;
+  const uint32_t lo = hdr[4], span = hdr[5] - lo;
+  uint32_t* L = lists + tab.score_off[seg];         // as long as the history: every list fits
+  uint32_t key[PER];
+  uint32_t c = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    key[j] = p0 + j * 64 < m ? score_key(pv[j]) : kKeyNone;
+    c += (uint32_t)__popcll(__ballot(key[j] - lo <= span));   // (kKeyNone - lo exceeds every span)
+  }
+  if (c) {
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&hdr[7], c);
+    base = (uint32_t)__shfl((int)base, 0, 64);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const bool in = key[j] - lo <= span;
+      const unsigned long long mask = __ballot(in);
+      if (in) L[base + lanes_below(mask)] = key[j];
+      base += (uint32_t)__popcll(mask);
+    }
+  }
 }
 
 // Ordered compaction of long histories, spread over the blocks of select_pool_kernel (one
@@ -2005,7 +2050,7 @@ static void launch_score(int pass, ScoreGrid grid, hipStream_t st, const TAB& ta
 
 template <class TAB>
 static void launch_select(int nseg, int blocks, hipStream_t st, const TAB& tab, const Geometry& g, const float* imp,
-                          float* pooled, uint32_t* blockhist, int32_t* kept_idx, int64_t* d_out_offsets,
+                          float* pooled, uint32_t* blockhist, uint32_t* lists, int32_t* kept_idx, int64_t* d_out_offsets,
                           const GatherArgs& ga) {
   const int radius = g.pool == SLKV_POOL_NONE ? 0 : g.pool_kernel / 2;
   const int pool_kernel = g.pool == SLKV_POOL_NONE ? 1 : g.pool_kernel;
@@ -2025,15 +2070,22 @@ static void launch_select(int nseg, int blocks, hipStream_t st, const TAB& tab, 
   // with blocks, the ordered compaction runs per block (two short launches over the whole chip)
   // instead of per segment inside the ranking workgroup
   const int split = blocks > 0 ? 1 : 0;
-  SLKV_LAUNCH(select_rank_kernel<TAB>, dim3(nseg), dim3(kSelThreads), 0, st, tab, g.w, (const float*)pooled,
-              blockhist, kept_idx, d_out_offsets, ga, split);
+  int64_t longest = 0;
+  for (const Seg& sg : g.segs) longest = std::max<int64_t>(longest, seg_blocks(sg, g.w));
+  // block-wise launches: a grid row per segment unless that would launch mostly empty workgroups
+  // (one long history among many short ones) or more rows than a grid has
+  const bool rows = nseg <= 65535 && longest * nseg <= 4 * (int64_t)blocks;
+  const dim3 grid = rows ? dim3((unsigned)std::max<int64_t>(longest, 1), (unsigned)nseg) : dim3((unsigned)std::max(blocks, 1));
   if (split) {
-    int64_t longest = 0;
-    for (const Seg& sg : g.segs) longest = std::max<int64_t>(longest, seg_blocks(sg, g.w));
-    // a grid row per segment unless that would launch mostly empty workgroups (one long history
-    // among many short ones) or more rows than a grid has
-    const bool rows = nseg <= 65535 && longest * nseg <= 4 * (int64_t)blocks;
-    const dim3 grid = rows ? dim3((unsigned)longest, (unsigned)nseg) : dim3((unsigned)blocks);
+    // first-level digit per segment, then the blocks list the scores of that digit
+    SLKV_LAUNCH(select_rank_kernel<TAB>, dim3(nseg), dim3(kSelThreads), 0, st, tab, g.w, (const float*)pooled,
+                blockhist, kept_idx, d_out_offsets, ga, split, (const uint32_t*)lists, 0);
+    SLKV_LAUNCH(select_collect_kernel<TAB>, grid, dim3(kSelEmitThreads), 0, st, tab, g.w, (const float*)pooled, blockhist,
+                lists, rows ? 0 : -1);
+  }
+  SLKV_LAUNCH(select_rank_kernel<TAB>, dim3(nseg), dim3(kSelThreads), 0, st, tab, g.w, (const float*)pooled,
+              blockhist, kept_idx, d_out_offsets, ga, split, (const uint32_t*)lists, 1);
+  if (split) {
     SLKV_LAUNCH(select_count_kernel<TAB>, grid, dim3(kSelEmitThreads), 0, st, tab, g.w, (const float*)pooled, blockhist,
                 rows ? 0 : -1);
     SLKV_LAUNCH(select_emit_kernel<TAB>, grid, dim3(kSelEmitThreads), 0, st, tab, g.w, (const float*)pooled,
@@ -2200,6 +2252,10 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
 
   uint32_t* tickets = (uint32_t*)ws;
   uint32_t* blockhist = (uint32_t*)(ws + p.off_hist);
+  // candidate lists of the block-wise selection: the workspace's importance area, which is either
+  // unused (the caller asked for the importance scores in an array of its own) or dead by then
+  // (pooling has consumed the scores)
+  uint32_t* lists = (uint32_t*)(ws + p.off_imp);
 
   // The kernels of the pass over the segments one table describes.
   // Selection kernel: if every history fits one round, the one-workgroup-per-segment kernel;
@@ -2235,7 +2291,7 @@ static slkv_status run_geometry(const Geometry& g, const void* d_qwin, const voi
         hipError_t se = launch_select_resident(nseg, st, tab, g, d_pooled != nullptr, imp, pooled, d_kept_idx, d_out_offsets, ga);
         if (se != hipSuccess) return fail(SLKV_ERR_HIP, "select launch setup failed: %s", hipGetErrorString(se));
       } else {
-        launch_select(nseg, blocks, st, tab, g, imp, pooled, blockhist, d_kept_idx, d_out_offsets, ga);
+        launch_select(nseg, blocks, st, tab, g, imp, pooled, blockhist, lists, d_kept_idx, d_out_offsets, ga);
       }
     }
     const bool gather_all = !resident_select && blocks > 0;   // the block-wise selection copies no rows itself
