@@ -753,18 +753,19 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const TAB tab, const flo
 // Pooling + top-k (Algorithm 3, steps 7-8).  Writes the kept positions: history positions
 // ascending, then the window.
 //
-// Histories longer than one round of kSelRound positions take four kernels (the last two are
-// described where they are defined):
-//   select_pool_kernel: the history is cut into blocks of kSelBlock positions, one workgroup each:
-//     pool the block's importance scores (halo from the neighbours), write the pooled scores,
-//     histogram their leading 11 key bits, write the block's histogram;
-//   select_rank_kernel: one workgroup per segment adds the block histograms, picks the digit that
-//     holds the k-th largest score, collects that digit's scores in LDS and narrows them down to
-//     the exact k-th largest value tau and the number of scores equal to tau that belong to the
-//     top k (ties go to lower positions), and leaves both for select_count_kernel and
-//     select_emit_kernel, which write the kept history positions block by block: those with
-//     score > tau, or == tau among the first `need_eq`.  The window's positions, and the
-//     positions of segments that are not ranked, are written here.
+// Histories longer than one round of kSelRound positions take six launches; whatever touches every
+// position runs with one workgroup per block of kSelBlock positions, only the digit searches run
+// per segment (the block-wise kernels are described where they are defined):
+//   select_pool_kernel: pool the block's importance scores (halo from the neighbours), write the
+//     pooled scores, histogram their leading 11 key bits, write the block's histogram;
+//   select_rank_kernel, phase 0: one workgroup per segment adds the block histograms and picks
+//     the digit that holds the k-th largest score;
+//   select_collect_kernel: the blocks copy their scores of that digit to the segment's list;
+//   select_rank_kernel, phase 1: narrows the list down to the exact k-th largest value tau and
+//     the number of scores equal to tau that belong to the top k (ties go to lower positions);
+//     it also writes the window's positions and those of segments that are not ranked;
+//   select_count_kernel, select_emit_kernel: the kept history positions, block by block: those
+//     with score > tau, or == tau among the first `need_eq`.
 // (One kernel with a per-segment ticket, the last block doing the ranking, was measured and
 // dropped: with 1024-thread workgroups at one per CU, the blocks of later segments queue behind
 // ranking workgroups and start tens of microseconds late.)
