@@ -877,12 +877,12 @@ __global__ __launch_bounds__(kSelThreads) void select_rank_kernel(const TAB tab,
   __shared__ uint32_t small_list[kSelRankMax];
   __shared__ int32_t sh_pos[kInlineGatherRows];
   __shared__ uint32_t sh_scan[NW];
-  __shared__ uint32_t sh_wg[NW], sh_we[NW];
   __shared__ uint32_t res[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int seg = blockIdx.x;
   const int bid = seg;
+  (void)bid;                                           // (only the development stamps use it)
   const int nblk = tab.blk_begin[seg + 1] - tab.blk_begin[seg];
   const int n = tab.n[seg];
   const int kk = tab.kkeep[seg];
