@@ -308,7 +308,7 @@ typedef enum {
   SLKV_K_SCORE_STATS = 0,   /* logits + per-row sum-exp of every key chunk */
   SLKV_K_COMBINE = 1,       /* not launched any more: the statistics pass folds the chunks itself */
   SLKV_K_SCORE_ACCUM = 2,   /* logits + exp(logit - lse) summed down the rows */
-  SLKV_K_SELECT = 3,        /* pooling + top-k */
+  SLKV_K_SELECT = 3,        /* pooling + top-k (one record per launch: one launch for histories up to 32768 positions, six for longer ones) */
   SLKV_K_GATHER = 4,        /* K/V row gather */
   SLKV_K_ROW_CELLS = 5,     /* Stage 1: per-row weight cells */
   SLKV_K_HEAD_REDUCE = 6,   /* Stage 1: per-head sums and scores */
