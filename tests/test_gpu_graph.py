@@ -133,3 +133,53 @@ def test_calls_on_two_streams_do_not_interfere():
         for i, call in enumerate(calls):
             for a, b in zip(outputs(call), refs[i]):
                 assert np.array_equal(a, b), (rep, i)
+
+
+def test_captured_block_wise_selection_replays_like_eager():
+    # the selection of long histories is six launches that hand their state on through the workspace
+    # (digit, list length, threshold, per-block counts): every replay has to start it afresh
+    import os
+    import torch
+    Hq, Hkv, d, w = 4, 2, 64, 16
+    lays = [wl.make_layer((304, i), [9000, 2600], Hq, Hkv, d, w, dtype="bf16", bias_frac=0.05) for i in range(3)]
+    bud = np.array([500, 90], dtype=np.int32)
+    old = os.environ.get("SLKV_SELECT")
+    os.environ["SLKV_SELECT"] = "blocks"
+    try:
+        call = api.LayerCall("bf16", 2, Hq, Hkv, d, w, lays[0].cu_seqlens, bud)
+        q = api.to_device(lays[0].qwin, "bf16")
+        k = api.to_device(lays[0].k, "bf16")
+        v = api.to_device(lays[0].v, "bf16")
+        refs = []
+        for lay in lays:
+            q.copy_(api.to_device(lay.qwin, "bf16")); k.copy_(api.to_device(lay.k, "bf16")); v.copy_(api.to_device(lay.v, "bf16"))
+            call.run(q, k, v)
+            torch.cuda.synchronize()
+            refs.append(outputs(call))
+        assert not np.array_equal(refs[0][2], refs[1][2])
+        B.slkv_init()
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            call.run(q, k, v)
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            call.run(q, k, v)
+    finally:
+        if old is None:
+            os.environ.pop("SLKV_SELECT", None)
+        else:
+            os.environ["SLKV_SELECT"] = old
+    for rep in range(2):
+        for i, lay in enumerate(lays):
+            q.copy_(api.to_device(lay.qwin, "bf16")); k.copy_(api.to_device(lay.k, "bf16")); v.copy_(api.to_device(lay.v, "bf16"))
+            call.kept_idx.fill_(-1)
+            call.k_out.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = outputs(call)
+            for a, b in zip(got, refs[i]):
+                assert np.array_equal(a, b), (rep, i)
